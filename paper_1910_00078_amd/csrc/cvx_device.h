@@ -1,0 +1,99 @@
+// Device-side helpers shared by the kernels: storage-type conversion and the fused epilogue
+// (bias, optional inference batch-norm, activation -- Sec. V and Tables I/II of the MIOpen paper).
+#pragma once
+#include "cvx_internal.h"
+
+namespace cvx {
+
+typedef _Float16 half_t;
+
+// ---- storage <-> fp32 ------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// Round to nearest, ties to even; NaN stays NaN (quiet).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
+{
+    half_t h = (half_t)f;                       // v_cvt_f16_f32: round to nearest even
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(half_t, b); }
+
+template <int DT> struct Elem;
+template <> struct Elem<DT_F32> {
+    typedef float type;
+    static __device__ __forceinline__ float load(const void* p, size_t i) { return ((const float*)p)[i]; }
+    static __device__ __forceinline__ void store(void* p, size_t i, float v) { ((float*)p)[i] = v; }
+};
+template <> struct Elem<DT_F16> {
+    typedef uint16_t type;
+    static __device__ __forceinline__ float load(const void* p, size_t i) { return f16_bits_to_f32(((const uint16_t*)p)[i]); }
+    static __device__ __forceinline__ void store(void* p, size_t i, float v) { ((uint16_t*)p)[i] = f32_to_f16_bits(v); }
+};
+template <> struct Elem<DT_BF16> {
+    typedef uint16_t type;
+    static __device__ __forceinline__ float load(const void* p, size_t i) { return bf16_bits_to_f32(((const uint16_t*)p)[i]); }
+    static __device__ __forceinline__ void store(void* p, size_t i, float v) { ((uint16_t*)p)[i] = f32_to_bf16_bits(v); }
+};
+
+// 16-bit storage conversion selected at compile time (DT_F16 or DT_BF16).
+template <int DT> __device__ __forceinline__ uint16_t f32_to_bits16(float v)
+{
+    return DT == DT_BF16 ? f32_to_bf16_bits(v) : f32_to_f16_bits(v);
+}
+template <int DT> __device__ __forceinline__ float bits16_to_f32(uint16_t b)
+{
+    return DT == DT_BF16 ? bf16_bits_to_f32(b) : f16_bits_to_f32(b);
+}
+
+// ---- epilogue ----------------------------------------------------------------------------------
+__device__ __forceinline__ float activate(float v, int act, float alpha)
+{
+    switch (act) {
+    case ACT_RELU:       return fmaxf(v, 0.0f);
+    case ACT_LEAKY_RELU: return v > 0.0f ? v : alpha * v;
+    case ACT_TANH:       return tanhf(v);
+    case ACT_LOGISTIC:   return 1.0f / (1.0f + expf(-v));
+    default:             return v;
+    }
+}
+
+// Per-output-channel affine form of the epilogue: y = act(acc * mul + add), with
+//   no batch-norm:  mul = 1,                          add = bias
+//   batch-norm:     mul = scale / sqrt(var + eps),    add = (bias - mean) * mul + shift
+struct ChannelAffine {
+    float mul, add;
+};
+
+template <int DT>
+__device__ __forceinline__ ChannelAffine channel_affine(const ConvArgs& a, int k)
+{
+    float b = 0.0f;
+    if (a.bias) b = a.bias_f32 ? ((const float*)a.bias)[k] : Elem<DT>::load(a.bias, k);
+    ChannelAffine r;
+    if (a.bn_scale) {
+        const float m = a.bn_scale[k] / sqrtf(a.bn_var[k] + a.bn_eps);
+        r.mul = m;
+        r.add = (b - a.bn_mean[k]) * m + a.bn_shift[k];
+    } else {
+        r.mul = 1.0f;
+        r.add = b;
+    }
+    return r;
+}
+
+__device__ __forceinline__ float finish(float acc, const ChannelAffine& ca, bool has_bn, int act, float alpha)
+{
+    const float v = has_bn ? fmaf(acc, ca.mul, ca.add) : acc + ca.add;
+    return activate(v, act, alpha);
+}
+
+}  // namespace cvx

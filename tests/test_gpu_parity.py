@@ -1,0 +1,191 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on the same
+seeded inputs, element by element.  Tolerances: fp32 relative L2 <= 1e-5; fp16/bf16 every element
+within 1e-2*|ref| + 1e-3*rms(ref)."""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from paper_1910_00078_amd import cvx
+
+from parity import run_gpu, run_oracle, tolerance_ok, to_device, to_host_f64, DT_CODE
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def check_case(w, *, policy=0, seed=wl.BASE_SEED, **kw):
+    say("case %s dtype=%s N=%d C=%d H=%d W=%d K=%d R=%d S=%d pad=%s stride=%s dil=%s g=%d policy=%d %s"
+        % (w.name, w.dtype, w.N, w.C, w.H, w.W, w.K, w.R, w.S, w.pad, w.stride, w.dil, w.groups, policy, kw))
+    x, wt, b = wl.make_inputs(w, seed)
+    got, name = run_gpu(w, x, wt, b, policy=policy, **kw)
+    okw = {k: v for k, v in kw.items() if k != "bias_f32"}
+    ref = run_oracle(w, x, wt, b, **okw)
+    assert got.shape == ref.shape
+    ok, msg = tolerance_ok(got, ref, w.dtype)
+    assert ok, "%s via %s: %s" % (w.name, name, msg)
+    return name
+
+
+# ---- the benchmark configurations at full size, in the launch configuration the bench times ----
+@pytest.mark.parametrize("name", ["c1", "c2", "c3a", "c3b", "c4", "c5a", "c5b"])
+def test_full_size_configs(name):
+    check_case(wl.WORKLOADS[name])
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c4"])
+def test_full_size_configs_generic_kernel(name):
+    w = wl.WORKLOADS[name]
+    if name != "c1":
+        w = wl.small_variant(w, N=2)
+    check_case(w, policy=1)
+
+
+# ---- reduced shapes that still span several tiles and ragged tails ----
+def _v(base, **kw):
+    return wl.small_variant(wl.WORKLOADS[base], **kw)
+
+
+SMALL = [
+    _v("c2", name="c2_n3", N=3),
+    _v("c2", name="c2_ragged", N=2, C=24, K=40, H=19, W=23),
+    _v("c2", name="c2_f16", N=2, dtype=wl.F16),
+    _v("c2", name="c2_f32", N=1, C=16, K=24, H=20, W=20, dtype=wl.F32),
+    _v("c3a", name="c3a_n2", N=2),
+    _v("c3b", name="c3b_n2", N=2),
+    _v("c3a", name="1x1_ragged", N=3, C=40, K=24, H=13, W=11),
+    _v("c3a", name="1x1_stride2", N=2, C=64, K=32, H=15, W=14, stride=(2, 2)),
+    _v("c4", name="c4_n2", N=2),
+    _v("c4", name="c4_ragged", N=2, H=61, W=45, K=24),
+    _v("c4", name="c4_bf16", N=1, H=64, W=64, dtype=wl.BF16),
+    _v("c5a", name="c5a_small", N=6, C=64, K=96),
+    _v("c5b", name="c5b_small", N=3, C=64, K=48),
+    _v("c5b", name="c5b_odd", N=2, C=32, K=32, H=27, W=25),
+    _v("c2", name="dil2", N=2, C=32, K=32, H=20, W=18, pad=(2, 2), dil=(2, 2)),
+    _v("c2", name="rect_filter", N=2, C=16, K=16, H=17, W=21, R=3, S=5, pad=(1, 2)),
+    _v("c2", name="asym", N=2, C=8, K=8, H=16, W=30, R=2, S=3, pad=(0, 2), stride=(2, 1), dil=(1, 2)),
+    _v("c2", name="big_pad", N=1, C=8, K=8, H=5, W=6, pad=(4, 5)),
+    _v("c2", name="5x5", N=2, C=16, K=32, H=14, W=14, R=5, S=5, pad=(2, 2)),
+    _v("c2", name="groups4", N=2, C=32, K=64, H=14, W=14, groups=4),
+    _v("c2", name="depthwise", N=2, C=32, K=32, H=14, W=14, groups=32),
+    _v("c1", name="c1_tiny_1x1img", H=1, W=1, pad=(1, 1)),
+    _v("c1", name="c1_C1K1", C=1, K=1),
+    _v("c2", name="c_not_mult8", N=2, C=20, K=12, H=9, W=9),
+    _v("c2", name="c3_k5", N=2, C=3, K=5, H=12, W=12),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+def test_reduced_shapes(w):
+    check_case(w)
+
+
+@pytest.mark.parametrize("w", SMALL[::3], ids=lambda w: w.name)
+def test_reduced_shapes_generic_kernel(w):
+    check_case(w, policy=1)
+
+
+# ---- epilogue variants ----
+@pytest.mark.parametrize("act,alpha", [(cvx.CVX_ACT_IDENTITY, 0.0), (cvx.CVX_ACT_RELU, 0.0),
+                                        (cvx.CVX_ACT_LEAKY_RELU, 0.1), (cvx.CVX_ACT_TANH, 0.0),
+                                        (cvx.CVX_ACT_LOGISTIC, 0.0)])
+@pytest.mark.parametrize("base", ["c2", "c1", "c4"])
+def test_activations(base, act, alpha):
+    w = wl.WORKLOADS[base]
+    if base != "c1":
+        w = wl.small_variant(w, N=2, H=min(w.H, 40), W=min(w.W, 40))
+    check_case(w, act=act, alpha=alpha)
+
+
+@pytest.mark.parametrize("base", ["c2", "c3a", "c1"])
+def test_no_bias_and_fp32_bias(base):
+    w = wl.WORKLOADS[base]
+    if base != "c1":
+        w = wl.small_variant(w, N=2)
+    check_case(w, use_bias=False, act=cvx.CVX_ACT_IDENTITY)
+    check_case(w, bias_f32=True)
+
+
+@pytest.mark.parametrize("base", ["c2", "c3b", "c1"])
+def test_batchnorm_epilogue(base):
+    w = wl.WORKLOADS[base]
+    if base != "c1":
+        w = wl.small_variant(w, N=2)
+    rng = np.random.default_rng(5)
+    bn = (rng.uniform(0.5, 1.5, w.K), rng.uniform(-0.5, 0.5, w.K), rng.uniform(-0.3, 0.3, w.K),
+          rng.uniform(0.5, 2.0, w.K))
+    bn = tuple(t.astype(np.float32).astype(np.float64) for t in bn)
+    check_case(w, bn=bn, eps=1e-3)
+
+
+def test_plain_conv_fwd_and_unfused_operators_agree_with_fused():
+    """conv_fwd, then bias_add, then activation as three launches (the unfused route of Sec. V)
+    lands within one output rounding per step of the fused call, and both within tolerance."""
+    import torch
+    w = wl.small_variant(wl.WORKLOADS["c2"], N=2)
+    x, wt, b = wl.make_inputs(w)
+    dx, dw, db = to_device(x, w.dtype), to_device(wt, w.dtype), to_device(b, w.dtype)
+    plan = cvx.ConvPlan(DT_CODE[w.dtype], tuple(dx.shape), tuple(dw.shape), w.pad, w.stride, w.dil)
+    y = torch.empty(plan.y_shape, dtype=dx.dtype, device="cuda")
+    plan.run_plain(dx.data_ptr(), dw.data_ptr(), y.data_ptr())
+    torch.cuda.synchronize()
+    ref_plain = run_oracle(w, x, wt, b, act=0, use_bias=False)
+    ok, msg = tolerance_ok(to_host_f64(y, w.dtype), ref_plain, w.dtype)
+    assert ok, msg
+    cvx.cvx_bias_add(plan.h, plan.bd, db.data_ptr(), plan.yd, y.data_ptr())
+    cvx.cvx_activation_fwd(plan.h, cvx.CVX_ACT_RELU, 0.0, plan.yd, y.data_ptr())
+    torch.cuda.synchronize()
+    ref = run_oracle(w, x, wt, b, act=1)
+    ok, msg = tolerance_ok(to_host_f64(y, w.dtype), ref, w.dtype)
+    assert ok, msg
+    plan.close()
+
+
+def test_repeated_runs_are_bit_identical():
+    import torch
+    for name in ("c2", "c3a", "c4", "c5b"):
+        w = wl.small_variant(wl.WORKLOADS[name], N=2)
+        x, wt, b = wl.make_inputs(w)
+        dx, dw, db = to_device(x, w.dtype), to_device(wt, w.dtype), to_device(b, w.dtype)
+        outs = [cvx.conv_fwd_fused(dx, dw, db, pad=w.pad, stride=w.stride, dil=w.dil) for _ in range(3)]
+        torch.cuda.synchronize()
+        for o in outs[1:]:
+            assert torch.equal(o.view(torch.int16), outs[0].view(torch.int16)), name
+
+
+def test_non_default_stream_and_reused_plan():
+    import torch
+    w = wl.small_variant(wl.WORKLOADS["c2"], N=2)
+    x, wt, b = wl.make_inputs(w)
+    dx, dw, db = to_device(x, w.dtype), to_device(wt, w.dtype), to_device(b, w.dtype)
+    ref = run_oracle(w, x, wt, b, act=1)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        plan = cvx.ConvPlan(DT_CODE[w.dtype], tuple(dx.shape), tuple(dw.shape), w.pad, w.stride, w.dil,
+                            stream=s.cuda_stream)
+        y = torch.empty(plan.y_shape, dtype=dx.dtype, device="cuda")
+        for _ in range(3):
+            plan.run(dx.data_ptr(), dw.data_ptr(), db.data_ptr(), y.data_ptr())
+        s.synchronize()
+        plan.close()
+    ok, msg = tolerance_ok(to_host_f64(y, w.dtype), ref, w.dtype)
+    assert ok, msg
+
+
+def test_compute_errors_are_reported_not_launched():
+    import torch
+    x = torch.zeros((1, 8, 6, 6), dtype=torch.bfloat16, device="cuda")
+    wt = torch.zeros((4, 8, 3, 3), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(cvx.CvxError) as e:
+        cvx.conv_fwd_fused(x, wt, torch.zeros(5, dtype=torch.bfloat16, device="cuda"), pad=1)
+    assert e.value.status == cvx.CVX_ERR_SHAPE_MISMATCH
+    with pytest.raises(cvx.CvxError) as e:
+        cvx.conv_fwd_fused(x, wt, None, pad=0, dil=4)
+    assert e.value.status == cvx.CVX_ERR_BAD_PARAM
+    with pytest.raises(ValueError):
+        cvx.conv_fwd_fused(x.cpu(), wt.cpu())
