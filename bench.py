@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused forward convolution (conv + bias + ReLU) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--all] [--no-cpu]
+
+A step is one cvx_conv_fwd_fused call on one batch of synthetic input already resident in HBM.
+Steps rotate over enough disjoint (x, y) buffer sets that the working set exceeds the 256 MiB
+Infinity Cache, so the figures are HBM figures.  The K timed steps are recorded once into HIP
+graphs (so the Python call overhead is not what is measured) and replayed between two HIP events
+on the launch stream, inside a wall-clock bracket with device synchronisation on both sides.
+
+Prints ONE JSON line.  `roofline` prices the kernel against the MI355X peak for its bound;
+`cpu_baseline` is the fp64 CPU oracle timed on this host in the same run (a reported baseline,
+not a target); `parity` is the check of the warm-up output against that oracle.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_MFMA_16BIT_TFLOPS = 2516.6      # dense bf16 / fp16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+ROTATE_BYTES = 1 << 30               # rotate buffer sets over at least this much memory
+GRAPH_CHUNK = 250
+
+# Which roofline binds each layer (arithmetic intensity against the 315 FLOP/byte ridge point,
+# see the design doc): the two 1x1 layers and the stem are HBM-bound, the 3x3 layers MFMA-bound.
+BOUND = {"c1": "alu", "c2": "mfma", "c3a": "hbm", "c3b": "hbm", "c4": "hbm", "c5a": "mfma", "c5b": "mfma"}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_workload(name: str, steps: int, warmup: int, check: bool):
+    import numpy as np
+    import torch
+    import workloads as wl
+    from paper_1910_00078_amd import cvx
+    from parity import to_device, to_host_f64, tolerance_ok, DT_CODE
+
+    w = wl.WORKLOADS[name]
+    x, wt, b = wl.make_inputs(w)
+    stream = torch.cuda.current_stream()
+    plan = cvx.ConvPlan(DT_CODE[w.dtype], (w.N, w.C, w.H, w.W), (w.K, w.C // w.groups, w.R, w.S),
+                        w.pad, w.stride, w.dil, w.groups, stream=stream.cuda_stream)
+    kernel = plan.kernel_name()
+    dw, db = to_device(wt, w.dtype), to_device(b, w.dtype)
+    x0 = to_device(x, w.dtype)
+    set_bytes = w.elem_bytes * (w.N * w.C * w.H * w.W + w.N * w.K * w.Ho * w.Wo)
+    nsets = min(64, max(2, -(-ROTATE_BYTES // set_bytes)))
+    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    ys = [torch.empty(plan.y_shape, dtype=x0.dtype, device="cuda") for _ in range(nsets)]
+
+    def step(i):
+        j = i % nsets
+        plan.run(xs[j].data_ptr(), dw.data_ptr(), db.data_ptr(), ys[j].data_ptr(), cvx.CVX_ACT_RELU, 0.0)
+
+    for i in range(max(warmup, 1)):
+        step(i)
+    torch.cuda.synchronize()
+
+    parity = None
+    ref = None
+    cpu = None
+    if check:
+        from oracle import conv_oracle
+        X, Wt, B = wl.to_f64(x, w.dtype), wl.to_f64(wt, w.dtype), wl.to_f64(b, w.dtype)
+        t0 = time.perf_counter()
+        ref = conv_oracle.conv_fwd(X, Wt, B, pad=w.pad, stride=w.stride, dil=w.dil, groups=w.groups, act=1)
+        dt = time.perf_counter() - t0
+        cpu = {"value": w.flops / dt / 1e12, "unit": "TFLOP/s", "cores": conv_oracle.threads(), "kind": "oracle",
+               "sample": "the whole %s workload once (%.2f GFLOP in %.2f s, fp64)" % (name, w.flops / 1e9, dt)}
+        ok, msg = tolerance_ok(to_host_f64(ys[0], w.dtype), ref, w.dtype)
+        parity = {"ok": bool(ok), "detail": msg}
+        log("[bench] parity %s: %s" % (name, msg))
+
+    # record the timed steps into graphs: chunks of GRAPH_CHUNK launches, replayed
+    chunk = min(steps, GRAPH_CHUNK)
+    reps, rem = divmod(steps, chunk)
+    side = torch.cuda.Stream()
+    graphs = []
+    for gi, n in enumerate([chunk] + ([rem] if rem else [])):
+        gph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            plan.set_stream(side.cuda_stream)
+            with torch.cuda.graph(gph, stream=side):
+                for i in range(n):
+                    step(gi * chunk + i)
+        graphs.append(gph)
+    plan.set_stream(stream.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    graphs[0].replay()                      # one untimed replay (graph upload)
+    torch.cuda.synchronize()
+
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(reps):
+        graphs[0].replay()
+    if rem:
+        graphs[1].replay()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ev_ms = e0.elapsed_time(e1)
+    plan.close()
+    return {"workload": w, "kernel": kernel, "wall_ms_per_step": wall_ms / steps, "event_ms_per_step": ev_ms / steps,
+            "nsets": nsets, "parity": parity, "cpu": cpu}
+
+
+def roofline(w, name, ms_kernel):
+    bound = BOUND[name]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(name)
+    if bound == "hbm":
+        ach = w.algorithmic_bytes / (ms_kernel * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                "traffic": traffic}
+    ach = w.flops / (ms_kernel * 1e-3) / 1e12
+    peak = PEAK_MFMA_16BIT_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
+    return {"bound": bound, "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--all", action="store_true", help="also time every layer; table to stderr and gpurun_out/bench_all.json")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (no parity check, no cpu_baseline)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (forward convolution shards over the batch with no "
+              "communication; see DESIGN.md); --gpus %d is not available" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    r = time_workload(args.workload, args.steps, args.warmup, check=not args.no_cpu)
+    w = r["workload"]
+    ms = r["event_ms_per_step"]
+    out = {
+        "metric": "conv-fwd TFLOP/s (fused bias+ReLU, bf16) and % of MFMA/HBM roofline",
+        "value": w.flops / (r["wall_ms_per_step"] * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["wall_ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "f16": "f16", "f32": "f32"}[w.dtype],
+        "data": "synthetic",
+        "config": {"workload": "%s: %s NCHW %dx%dx%dx%d -> K=%d, %dx%d filter, pad %d, stride %d, bias+ReLU"
+                               % (args.workload, w.dtype, w.N, w.C, w.H, w.W, w.K, w.R, w.S, w.pad[0], w.stride[0]),
+                   "kernel": r["kernel"], "buffer_sets": r["nsets"],
+                   "gflop_per_step": w.flops / 1e9, "algorithmic_mb_per_step": w.algorithmic_bytes / 1e6},
+        "roofline": roofline(w, args.workload, ms),
+        "cpu_baseline": r["cpu"],
+        "parity": r["parity"],
+        "event_ms_per_step": ms,
+    }
+
+    if args.all:
+        rows = []
+        for name in ["c1", "c2", "c3a", "c3b", "c4", "c5a", "c5b"]:
+            steps = 200 if name in ("c3a", "c3b", "c4") else 500
+            rr = time_workload(name, steps, 5, check=False)
+            ww = rr["workload"]
+            rf = roofline(ww, name, rr["event_ms_per_step"])
+            row = {"workload": name, "kernel": rr["kernel"], "us": rr["event_ms_per_step"] * 1e3,
+                   "tflops": ww.flops / (rr["event_ms_per_step"] * 1e-3) / 1e12,
+                   "gbs": ww.algorithmic_bytes / (rr["event_ms_per_step"] * 1e-3) / 1e9,
+                   "bound": rf["bound"], "frac": rf["frac"]}
+            rows.append(row)
+            log("[bench] %-4s %-28s %9.2f us  %8.1f TFLOP/s  %8.1f GB/s  %s frac %.3f"
+                % (name, row["kernel"], row["us"], row["tflops"], row["gbs"], row["bound"], row["frac"]))
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        json.dump(rows, open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w"), indent=1)
+        out["layers"] = rows
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -21,6 +21,7 @@ HEADERS = ["cvx_internal.h", "cvx_device.h", os.path.join("..", "..", "include",
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
+    "-mllvm", "-amdgpu-mfma-vgpr-form",   # MFMA accumulators stay in VGPRs: no AGPR<->VGPR copies around the k-loop
     "-Wno-unused-command-line-argument",
 ]
 
@@ -43,7 +44,13 @@ def _stale(target: str, deps) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = False, verbose: bool = False) -> str:
+def build(force: bool = False, verbose: bool = False, defines=(), lib_path: str = LIB, obj_dir: str = OBJ) -> str:
+    """Compile csrc/ into the shared library.  `defines` adds -D flags (developer builds, written to
+    another lib_path / obj_dir so the product library is untouched)."""
+    return _build(force, verbose, list(defines), lib_path, obj_dir)
+
+
+def _build(force, verbose, defines, LIB, OBJ) -> str:
     os.makedirs(OBJ, exist_ok=True)
     hipcc = _hipcc()
     hdrs = _extra_headers() + [os.path.join(CSRC, HEADERS[2])]
@@ -54,7 +61,7 @@ def build(force: bool = False, verbose: bool = False) -> str:
         o = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
         objs.append(o)
         if force or _stale(o, [s] + hdrs):
-            jobs.append([hipcc, "-x", "hip", "-c", s, "-o", o] + FLAGS)
+            jobs.append([hipcc, "-x", "hip", "-c", s, "-o", o] + FLAGS + ["-D" + d for d in defines])
 
     def run(cmd):
         if verbose:

@@ -1,6 +1,770 @@
-// placeholder until the MFMA kernel lands
+// Implicit-GEMM forward convolution on bf16 / fp16 MFMA for gfx950 (MI355X).
+//
+// The structure is the one Fig. 2 of the MIOpen paper draws for its composable-kernel implicit
+// GEMM -- blockwise slices of W and I from device memory into LDS, threadwise slices from LDS into
+// registers, accumulation of O in registers over (C-chunk, Y, X), one copy of O back to device
+// memory -- with the bias + activation epilogue of Sec. V applied to the accumulators before that
+// single store.  The mapping onto the hardware is this library's own:
+//
+//   GEMM view        D[k][pix] = sum_{tap, c} Wt[k][tap][c] * X[pix @ tap][c]
+//   MFMA             v_mfma_f32_32x32x16 (bf16 or f16 in, fp32 accumulate): A = 32 filters x 16
+//                    channels, B = 16 channels x 32 pixels; a lane supplies 8 consecutive channels.
+//   Input in LDS     channel-octet major: [octet][image][flat (h,w) element] with 16 bytes (8
+//                    channels) per element, so an MFMA operand is one ds_read_b128 and the filter
+//                    taps are plain address offsets.  NCHW keeps W contiguous, channels strided,
+//                    so the loader reads 8 channel rows with 16-byte loads along W and transposes
+//                    8x8 in registers (v_perm_b32) before 8 ds_write_b128.
+//   Padding          rows outside the image are zero-filled by the loader; columns outside the
+//                    image are redirected at read time to a 16-byte slot of zeros.
+//   Filters in LDS   [tap][octet][filter] x 16 bytes, transposed in registers the same way.
+//   Pipeline         two LDS stage buffers; global loads of stage s+1 are in flight while stage s
+//                    is multiplied.
 #include "cvx_device.h"
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
 namespace cvx {
-bool igemm_supported(const ConvArgs&, const char**) { return false; }
-hipError_t launch_igemm(const ConvArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// Developer facility, compiled out unless CVX_PHASE_TRACE is defined: thread 0 of every block
+// records wall-clock timestamps (100 MHz) at phase boundaries into a caller-provided buffer of
+// 32 slots per block (16 wall-clock stamps, then 16 shader-clock stamps).
+#ifdef CVX_PHASE_TRACE
+__device__ unsigned long long* g_phase_trace = nullptr;
+#define CVX_TRACE_MARK(slot)                                                                      \
+    do {                                                                                          \
+        if (threadIdx.x == 0 && g_phase_trace) {                                                  \
+            g_phase_trace[(size_t)blockIdx.x * 32 + (slot)] = wall_clock64();                     \
+            g_phase_trace[(size_t)blockIdx.x * 32 + 16 + (slot)] = clock64();                     \
+        }                                                                                         \
+    } while (0)
+#else
+#define CVX_TRACE_MARK(slot) do { } while (0)
+#endif
+
+// Division of small non-negative integers by a runtime divisor chosen on the host: q = n / d for
+// n, d < 65536 via one multiply-high (m = ceil(2^32 / d); exact while n * d < 2^32).
+struct FastDiv {
+    uint32_t m, d;
+    __device__ __forceinline__ int div(int n) const { return d == 1u ? n : (int)__umulhi((uint32_t)n, m); }
+};
+
+struct IgemmGeom {
+    int NB;          // images per pixel tile
+    int TH;          // output rows per pixel tile (tiles span the full output width)
+    int PH;          // input rows a tile needs: (TH-1)*stride_h + (R-1)*dil_h + 1
+    int WP;          // LDS row pitch in elements: W + 2*pad_w (the pad columns stay zero)
+    int UPI;         // loader units (8 flat elements x 8 channels) per (octet, image)
+    int SLOTS;       // LDS elements per (octet, image) = PH * WP
+    int row_blocks, img_blocks, k_blocks;
+    int n_stages;    // ceil(C / CC)
+    int a_units;     // input loader units per stage
+    int b_units;     // filter loader units per stage (register-transposed path)
+    int xbytes, wbytes;   // LDS bytes per stage for input and filters
+    FastDiv by_wo, by_w, by_upi, by_nb, by_kblocks, by_rowblocks;
+};
+
+template <int DT>
+__device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c)
+{
+    if constexpr (DT == DT_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
+
+// 16-byte load of 8 consecutive 16-bit elements starting at element offset `off` of a tensor with
+// `total` elements; elements outside the tensor read as zero.  Addresses are only 2-byte aligned.
+__device__ __forceinline__ u32x4 load8(const uint16_t* base, long long off, long long total)
+{
+    if (off >= 0 && off + 8 <= total) return *(const u32x4_a2*)(base + off);
+    u32x4 v = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const long long o = off + e;
+        if (o >= 0 && o < total) v[e >> 1] |= ((uint32_t)base[o]) << ((e & 1) * 16);
+    }
+    return v;
+}
+
+// Two fp32 values -> one dword of two bf16 / fp16 values (lo in bits 0..15), round to nearest even
+// in hardware (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+template <int DT>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    if constexpr (DT == DT_BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
+// result = (half `hb` of b) | (half `ha` of a) << 16
+__device__ __forceinline__ uint32_t pack_halves(uint32_t a, int ha, uint32_t b, int hb)
+{
+    const uint32_t sel = ((ha ? 0x0706u : 0x0504u) << 16) | (hb ? 0x0302u : 0x0100u);
+    return __builtin_amdgcn_perm(a, b, sel);
+}
+
+// LDS map (bytes): two stage buffers from offset 16, each an input region (xbytes, whose last 16
+// bytes are a trash slot for loader writes that must not land in the image) followed by a filter
+// region (wbytes).  After the last stage the same memory holds the output tile for the store.
+template <int DT, int WM, int WN, int TM, int TN, int CC, int TAPS, int UA, int UB>
+__global__ void __launch_bounds__(WM * WN * 64)
+igemm_kernel(ConvArgs a, IgemmGeom g)
+{
+    constexpr int THREADS = WM * WN * 64;
+    constexpr int KT = WN * TN * 32;       // filters per block   (MFMA B operand / D columns)
+    constexpr int PT = WM * TM * 32;       // pixels per block    (MFMA A operand / D rows)
+    constexpr int OCT = CC / 8;
+    constexpr int KSTEPS = CC / 16;
+    constexpr int PTP = PT + 8;            // pixel pitch of the staged output tile
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int BUF0 = 16;
+
+    CVX_TRACE_MARK(0);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm = wave / WN, wn = wave % WN;
+    const int taps = TAPS > 0 ? TAPS : a.R * a.S;
+    const int HW = a.H * a.W, HoWo = a.Ho * a.Wo;
+    const long long x_total = (long long)a.N * a.C * HW;
+    const long long w_total = (long long)a.K * a.C * taps;
+    const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
+    const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
+
+    // ---- which tile: consecutive logical ids stay on one XCD (hardware deals blocks round-robin
+    //      over the 8 XCDs), and blocks that share an input tile (differing only in the filter
+    //      block) are neighbours, so the shared tile is fetched into that XCD's L2 once.
+    int lid = blockIdx.x;
+    {
+        const int nblk = gridDim.x;
+        if ((nblk & 7) == 0) lid = (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3);
+    }
+    const int pb = g.by_kblocks.d == 1u ? lid : lid / (int)g.by_kblocks.d;
+    const int kb = lid - pb * (int)g.by_kblocks.d;
+    const int ib = g.by_rowblocks.d == 1u ? pb : pb / (int)g.by_rowblocks.d;
+    const int rb = pb - ib * (int)g.by_rowblocks.d;
+    const int k0 = kb * KT;
+    const int n0 = ib * g.NB;
+    const int p0 = rb * g.TH;
+    const int rows = min(g.TH, a.Ho - p0);
+    const int nimg = min(g.NB, a.N - n0);
+    const int ppi = rows * a.Wo;                       // output pixels per image in this tile
+    const int h_lo = p0 * a.stride_h - a.pad_h;        // first input row of the patch (may be < 0)
+    const int e_lo = h_lo * a.W;                       // flat element index of the patch start
+    const int n_ptiles = (nimg * ppi + 31) >> 5;       // pixel tiles holding at least one pixel
+
+    // ---- loader bookkeeping, part 1: what each thread fetches (needed before the first loads).
+    //      An input unit is 8 consecutive flat (h,w) elements of the patch for the 8 channels of
+    //      one octet.  A filter unit is (filter, octet): 8 channels x TAPS taps, contiguous in memory.
+    long long a_goff[UA];
+    int a_oct[UA], a_img[UA], a_ui[UA];
+#pragma unroll
+    for (int u = 0; u < UA; ++u) {
+        const int ua = tid + u * THREADS;
+        a_oct[u] = -1;
+        a_goff[u] = 0;
+        a_img[u] = 0;
+        a_ui[u] = 0;
+        if (ua < g.a_units) {
+            const int t = g.by_upi.div(ua);
+            const int ui = ua - t * g.UPI;
+            const int oct = g.by_nb.div(t);
+            const int img = t - oct * g.NB;
+            a_oct[u] = oct;
+            a_img[u] = img;
+            a_ui[u] = ui;
+            a_goff[u] = ((long long)(n0 + img) * a.C + oct * 8) * HW + e_lo + ui * 8;
+        }
+    }
+    constexpr int BROWS = TAPS > 0 ? (8 * TAPS * 2 + 15) / 16 : 1;   // 16-byte loads per filter unit
+    int b_k[UB], b_oct[UB];
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+        const int ub = tid + u * THREADS;
+        b_k[u] = ub % KT;
+        b_oct[u] = ub / KT;
+        if (ub >= g.b_units) b_oct[u] = -1;
+    }
+
+    u32x4 ra[UA][8];
+    u32x4 rbv[UB][BROWS];
+
+    // Global loads only; nothing here consumes a loaded value, so all of a stage's loads are in
+    // flight together and are first waited on in store_stage.
+    auto load_stage = [&](int st) {
+        const int cbase = st * CC;
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            if (a_oct[u] >= 0) {
+                const int c0 = cbase + a_oct[u] * 8;
+                const long long off0 = a_goff[u] + (long long)cbase * HW;
+                const bool fast = off0 >= 0 && off0 + 7LL * HW + 8 <= x_total && c0 + 8 <= a.C;
+                if (fast) {
+#ifdef CVX_EXP_NO_XLOAD
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) ra[u][j] = u32x4{(uint32_t)j, 0u, 0u, 0u};
+#else
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) ra[u][j] = *(const u32x4_a2*)(xg + off0 + (long long)j * HW);
+#endif
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        u32x4 v = {0u, 0u, 0u, 0u};
+                        if (c0 + j < a.C) v = load8(xg, off0 + (long long)j * HW, x_total);
+                        ra[u][j] = v;
+                    }
+                }
+            }
+        }
+        if constexpr (TAPS > 0) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                if (b_oct[u] >= 0) {
+                    const int k = k0 + b_k[u];
+                    const int c0 = cbase + b_oct[u] * 8;
+                    const long long off0 = ((long long)k * a.C + c0) * TAPS;
+                    const bool full = k < a.K && c0 + 8 <= a.C;
+                    if (full) {
+#pragma unroll
+                        for (int i = 0; i < BROWS; ++i) {
+#ifdef CVX_EXP_NO_WLOAD
+                            rbv[u][i] = u32x4{(uint32_t)i, 0u, 0u, 0u};
+                            continue;
+#endif
+                            if (i * 8 + 8 <= 8 * TAPS) rbv[u][i] = *(const u32x4_a2*)(wg + off0 + i * 8);
+                            else rbv[u][i] = load8(wg, off0 + i * 8, w_total);
+                        }
+                    } else {
+                        // ragged: filters past K or channels past C contribute zeros
+#pragma unroll
+                        for (int i = 0; i < BROWS; ++i) {
+                            u32x4 v = {0u, 0u, 0u, 0u};
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                const int t = i * 8 + e;          // = j * TAPS + tap
+                                const int j = t / TAPS;
+                                if (k < a.K && j < 8 && c0 + j < a.C)
+                                    v[e >> 1] |= ((uint32_t)wg[off0 + t]) << ((e & 1) * 16);
+                            }
+                            rbv[u][i] = v;
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    CVX_TRACE_MARK(1);
+    load_stage(0);
+
+    // ---- everything below up to the first barrier overlaps the latency of those loads --------
+
+    // loader bookkeeping, part 2: a_dst holds the LDS byte offset (inside the input region) that
+    // each of a unit's 8 elements goes to; elements outside the image go to the trash slot.
+    int a_dst[UA][8];
+#pragma unroll
+    for (int u = 0; u < UA; ++u) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a_dst[u][e] = g.xbytes - 16;
+        if (a_oct[u] >= 0) {
+            const int rel0 = a_ui[u] * 8;
+            int row = g.by_w.div(rel0);
+            int col = rel0 - row * a.W;
+            const int base = (a_oct[u] * g.NB + a_img[u]) * g.SLOTS + a.pad_w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int eabs = e_lo + rel0 + e;
+                if (a_img[u] < nimg && eabs >= 0 && eabs < HW && row < g.PH)
+                    a_dst[u][e] = (base + row * g.WP + col) * 16;
+                if (++col == a.W) { col = 0; ++row; }
+            }
+        }
+    }
+
+    CVX_TRACE_MARK(9);
+    // per-lane LDS byte offset of tap (0,0), octet `half`, for each of the wave's pixel tiles
+    const int oct_bytes = g.NB * g.SLOTS * 16;
+    int xbase[TM];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int f = (wm * TM + tm) * 32 + l32;
+        int img = 0, rem = f;
+        if (g.NB > 1) {                 // multi-image tiles hold whole images: ppi = Ho * Wo
+            img = f / ppi;
+            rem = f - img * ppi;
+        }
+        const int py = g.by_wo.div(rem);
+        const int px = rem - py * a.Wo;
+        const bool valid = f < nimg * ppi;
+        xbase[tm] = (valid ? (img * g.SLOTS + py * a.stride_h * g.WP + px * a.stride_w) * 16 : 0) + half * oct_bytes;
+    }
+    const int b_lane = ((wn * TN) * 32 + l32 + half * KT) * 16;
+    const bool wave_on = (wm * TM) < n_ptiles;         // this wave owns at least one live pixel tile
+
+    CVX_TRACE_MARK(10);
+    // epilogue constants of this lane's filters; without batch-norm the bias seeds the accumulators
+    const bool has_bn = a.bn_scale != nullptr;
+    ChannelAffine ca[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(k0 + (wn * TN + tn) * 32 + l32, a.K - 1));
+
+    CVX_TRACE_MARK(11);
+    {
+        // zero both input regions: pad columns and rows outside the image are never written
+        // afterwards, so they stay zero for every stage
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int i = tid * 16; i < g.xbytes; i += THREADS * 16) {
+            *(u32x4*)(smem + BUF0 + i) = z;
+            *(u32x4*)(smem + BUF0 + g.xbytes + g.wbytes + i) = z;
+        }
+    }
+
+    auto store_stage = [&](int st, int buf) {
+        unsigned char* xs = smem + BUF0 + buf * (g.xbytes + g.wbytes);
+        unsigned char* ws = xs + g.xbytes;
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            if (a_oct[u] >= 0) {
+                // 8 channel rows x 8 elements  ->  8 elements x 8 channels
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    u32x4 o;
+#pragma unroll
+                    for (int m = 0; m < 4; ++m)
+                        o[m] = pack_halves(ra[u][2 * m + 1][e >> 1], e & 1, ra[u][2 * m][e >> 1], e & 1);
+                    *(u32x4*)(xs + a_dst[u][e]) = o;
+                }
+            }
+        }
+        if constexpr (TAPS > 0) {
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                if (b_oct[u] >= 0) {
+#pragma unroll
+                    for (int tap = 0; tap < TAPS; ++tap) {
+                        u32x4 o;
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) {
+                            const int t0 = (2 * m) * TAPS + tap, t1 = (2 * m + 1) * TAPS + tap;
+                            o[m] = pack_halves(rbv[u][t1 >> 3][(t1 >> 1) & 3], t1 & 1,
+                                               rbv[u][t0 >> 3][(t0 >> 1) & 3], t0 & 1);
+                        }
+                        *(u32x4*)(ws + ((tap * OCT + b_oct[u]) * KT + b_k[u]) * 16) = o;
+                    }
+                }
+            }
+        } else {
+            // any filter size: element-wise gather from global memory, scatter into LDS
+            const int cbase = st * CC;
+            for (int pi = tid; pi < KT * CC; pi += THREADS) {
+                const int cl = pi % CC, kl = pi / CC;
+                const int k = k0 + kl, c = cbase + cl;
+                const bool ok = k < a.K && c < a.C;
+                const long long off0 = ((long long)k * a.C + c) * taps;
+                for (int t = 0; t < taps; ++t) {
+                    const uint16_t v = ok ? wg[off0 + t] : (uint16_t)0;
+                    *(uint16_t*)(ws + ((t * OCT + (cl >> 3)) * KT + kl) * 16 + (cl & 7) * 2) = v;
+                }
+            }
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const float seed = has_bn ? 0.0f : ca[tn].add;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
+        }
+
+    // One k-step = one filter tap x 16 channels: TM pixel fragments (MFMA A operand), TN filter
+    // fragments (B operand), TM*TN MFMAs.  The instruction order is pinned: after each of the first
+    // TM+TN MFMAs of a step, one fragment of the NEXT step is read (filters first, then pixels in
+    // the order the MFMAs will want them), so LDS latency hides behind the matrix pipe and the
+    // waits the compiler inserts are partial.
+    auto compute_stage = [&](int buf) {
+        if (!wave_on) return;
+        const unsigned char* xs = smem + BUF0 + buf * (g.xbytes + g.wbytes);
+        const unsigned char* ws = xs + g.xbytes + b_lane;
+        if constexpr (TAPS == 9 || TAPS == 1) {
+            constexpr int NS = TAPS * KSTEPS;
+            const int S3 = TAPS == 9 ? a.S : 1;
+            auto tap_bytes = [&](int tap) {
+                const int r = TAPS == 9 ? (S3 == 3 ? tap / 3 : tap / S3) : 0;
+                const int s = tap - r * S3;
+                return (r * a.dil_h * g.WP + s * a.dil_w) * 16;
+            };
+            u32x4 fa[2][TM], fb[2][TN];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(ws + tn * 32 * 16);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) fa[0][tm] = *(const u32x4*)(xs + xbase[tm]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NS; ++i) {
+                const int b = i & 1, nb = b ^ 1;
+                const bool more = i + 1 < NS;
+                const int ntap = (i + 1) / KSTEPS, nkk = (i + 1) % KSTEPS;
+                const int xo = more ? 2 * nkk * oct_bytes + tap_bytes(ntap) : 0;
+                int issued = 0;
+                auto read_next = [&]() {
+                    if (issued < TN) fb[nb][issued] = *(const u32x4*)(ws + ((ntap * OCT + 2 * nkk) * KT + issued * 32) * 16);
+                    else fa[nb][issued - TN] = *(const u32x4*)(xs + xbase[issued - TN] + xo);
+                    ++issued;
+                };
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) {
+                        acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (more && issued < TM + TN) {
+                            read_next();
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < TM + TN; ++j) {
+                    if (more && issued < TM + TN) {
+                        read_next();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+        } else {
+            int r = 0, s = 0;
+            for (int tap = 0; tap < taps; ++tap) {
+                const int tap_off = (r * a.dil_h * g.WP + s * a.dil_w) * 16;
+#pragma unroll
+                for (int kk = 0; kk < KSTEPS; ++kk) {
+                    u32x4 fa[TM], fb[TN];
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) fb[tn] = *(const u32x4*)(ws + ((tap * OCT + 2 * kk) * KT + tn * 32) * 16);
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) fa[tm] = *(const u32x4*)(xs + xbase[tm] + 2 * kk * oct_bytes + tap_off);
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma_32x32x16<DT>(fa[tm], fb[tn], acc[tm][tn]);
+                }
+                if (++s == a.S) { s = 0; ++r; }
+            }
+        }
+    };
+
+    // ---- main pipeline
+    CVX_TRACE_MARK(12);
+    __syncthreads();
+    CVX_TRACE_MARK(13);
+    store_stage(0, 0);
+    CVX_TRACE_MARK(14);
+    __syncthreads();
+    CVX_TRACE_MARK(2);
+    for (int st = 0; st < g.n_stages; ++st) {
+        const int buf = st & 1;
+        const bool more = st + 1 < g.n_stages;
+        if (more) load_stage(st + 1);
+        compute_stage(buf);
+        if (st < 6) CVX_TRACE_MARK(3 + 2 * st);
+        if (more) store_stage(st + 1, buf ^ 1);
+        __syncthreads();
+        if (st < 6) CVX_TRACE_MARK(4 + 2 * st);
+    }
+
+    // ---- epilogue: batch-norm / activation on the accumulators in registers, one rounding to the
+    //      output type, then the tile goes through LDS as [filter][pixel] so that the single store
+    //      to device memory is 16 bytes per lane along the pixel axis.
+    uint16_t* ot = (uint16_t*)(smem + BUF0);
+    if (wave_on) {
+        auto stage_out = [&](auto&& act_fn) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int kl = (wn * TN + tn) * 32 + l32;
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        float v[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float t = acc[tm][tn][4 * q4 + j];
+                            v[j] = act_fn(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t);
+                        }
+                        const int f = (wm * TM + tm) * 32 + 8 * q4 + 4 * half;
+                        *(uint2*)(ot + kl * PTP + f) = make_uint2(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]));
+                    }
+                }
+            }
+        };
+        if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
+        else if (a.act == ACT_IDENTITY) stage_out([](float t) { return t; });
+        else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
+    }
+    __syncthreads();
+    {
+        constexpr int CH = PT / 8;                 // 8-pixel chunks per filter row
+        constexpr int RSTEP = THREADS / CH;        // filter rows covered per pass
+        constexpr int NPASS = KT / RSTEP;
+        const int chunk = tid % CH, row0 = tid / CH;
+        const int f0 = chunk * 8;
+        const int npix = nimg * ppi;
+        if (f0 < npix) {
+            int img = 0, rem = f0;
+            if (g.NB > 1) {
+                img = f0 / ppi;
+                rem = f0 - img * ppi;
+            }
+            const bool whole = rem + 8 <= ppi;     // all 8 pixels valid and inside one image
+            uint16_t* __restrict__ yg = (uint16_t*)a.y;
+            const size_t obase = ((size_t)(n0 + img) * a.K + k0) * HoWo + (size_t)p0 * a.Wo + rem;
+            constexpr int GRP = NPASS >= 4 ? 4 : NPASS;
+            for (int p = 0; p < NPASS; p += GRP) {
+                u32x4 v[GRP];
+#pragma unroll
+                for (int j = 0; j < GRP; ++j) v[j] = *(const u32x4*)(ot + (row0 + (p + j) * RSTEP) * PTP + f0);
+#pragma unroll
+                for (int j = 0; j < GRP; ++j) {
+                    const int kl = row0 + (p + j) * RSTEP;
+                    if (k0 + kl < a.K) {
+                        uint16_t* dst = yg + obase + (size_t)kl * HoWo;
+                        if (whole) {
+                            *(u32x4_a2*)dst = v[j];
+                        } else {
+                            // chunk straddles an image boundary or the end of the tile: element-wise
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                const int f = f0 + e;
+                                if (f < npix) {
+                                    int im2 = 0, rm2 = f;
+                                    if (g.NB > 1) {
+                                        im2 = f / ppi;
+                                        rm2 = f - im2 * ppi;
+                                    }
+                                    yg[((size_t)(n0 + im2) * a.K + k0 + kl) * HoWo + (size_t)p0 * a.Wo + rm2] =
+                                        (uint16_t)(v[j][e >> 1] >> ((e & 1) * 16));
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    CVX_TRACE_MARK(15);
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side: tile geometry, variant table, launch
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int LDS_LIMIT = 160 * 1024;
+
+struct Variant {
+    const char* name;
+    int WM, WN, TM, TN, CC, TAPS, UA, UB;     // waves / tiles along pixels (M) and filters (N)
+    void (*kern_bf16)(ConvArgs, IgemmGeom);
+    void (*kern_f16)(ConvArgs, IgemmGeom);
+};
+
+#define IGEMM_VARIANT(nm, WM, WN, TM, TN, CC, TAPS, UA, UB)                                          \
+    {nm, WM, WN, TM, TN, CC, TAPS, UA, UB, igemm_kernel<DT_BF16, WM, WN, TM, TN, CC, TAPS, UA, UB>, \
+     igemm_kernel<DT_F16, WM, WN, TM, TN, CC, TAPS, UA, UB>}
+
+// name: igemm_<pixels per block>x<filters per block>_c<channels per stage>_<taps>
+const Variant kVariants[] = {
+    IGEMM_VARIANT("igemm_512x64_c32_3x3", 4, 1, 4, 2, 32, 9, 1, 1),
+    IGEMM_VARIANT("igemm_512x64_c16_3x3", 4, 1, 4, 2, 16, 9, 1, 1),
+    IGEMM_VARIANT("igemm_256x64_c32_3x3", 4, 1, 2, 2, 32, 9, 1, 1),
+    IGEMM_VARIANT("igemm_256x64_c16_3x3", 4, 1, 2, 2, 16, 9, 1, 1),
+    IGEMM_VARIANT("igemm_256x64_c16_3x3_u2", 4, 1, 2, 2, 16, 9, 2, 1),
+    IGEMM_VARIANT("igemm_512x64_c32_1x1", 4, 1, 4, 2, 32, 1, 1, 1),
+    IGEMM_VARIANT("igemm_256x64_c32_1x1", 4, 1, 2, 2, 32, 1, 1, 1),
+    IGEMM_VARIANT("igemm_256x64_c32_1x1_u2", 4, 1, 2, 2, 32, 1, 2, 1),
+    IGEMM_VARIANT("igemm_256x64_c16_any", 4, 1, 2, 2, 16, 0, 2, 1),
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+FastDiv fast_div(int d)
+{
+    FastDiv f;
+    f.d = (uint32_t)d;
+    f.m = d > 1 ? (uint32_t)(((1ull << 32) + (uint32_t)d - 1) / (uint32_t)d) : 0u;
+    return f;
+}
+
+int lds_bytes(const Variant& v, const IgemmGeom& g)
+{
+    const int KT = v.WN * v.TN * 32, PT = v.WM * v.TM * 32;
+    const int stages = 16 + 2 * (g.xbytes + g.wbytes);
+    const int otile = 16 + KT * (PT + 8) * 2;
+    return stages > otile ? stages : otile;
+}
+
+// Tile geometry for a variant with a given pixel-tile shape (NB images x TH output rows, full
+// width); returns false if the problem does not fit the variant that way.
+bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
+{
+    const int taps = a.R * a.S;
+    if (v.TAPS > 0 && v.TAPS != taps) return false;
+    const int threads = v.WM * v.WN * 64;
+    const int KT = v.WN * v.TN * 32, PT = v.WM * v.TM * 32, OCT = v.CC / 8;
+    if (NB < 1 || TH < 1 || NB > a.N || TH > a.Ho) return false;
+    if (NB > 1 && TH != a.Ho) return false;
+    if ((long long)NB * TH * a.Wo > PT) return false;
+    if (a.W >= 32768 || a.Wo >= 32768) return false;
+    IgemmGeom g;
+    g.NB = NB;
+    g.TH = TH;
+    g.PH = (g.TH - 1) * a.stride_h + (a.R - 1) * a.dil_h + 1;
+    g.WP = a.W + 2 * a.pad_w;
+    const long long slots = (long long)g.PH * g.WP;
+    const long long upi = ((long long)g.PH * a.W + 7) / 8;
+    if (slots > 65535 || upi > 65535) return false;
+    g.UPI = (int)upi;
+    g.SLOTS = (int)slots;
+    g.row_blocks = (a.Ho + g.TH - 1) / g.TH;
+    g.img_blocks = (a.N + g.NB - 1) / g.NB;
+    g.k_blocks = (a.K + KT - 1) / KT;
+    g.n_stages = (a.C + v.CC - 1) / v.CC;
+    const long long a_units = (long long)OCT * g.NB * g.UPI;
+    if (a_units > (long long)v.UA * threads) return false;
+    g.a_units = (int)a_units;
+    g.b_units = v.TAPS > 0 ? KT * OCT : 0;
+    if (g.b_units > v.UB * threads) return false;
+    const long long xb = (long long)OCT * g.NB * g.SLOTS * 16 + 16, wb = (long long)taps * OCT * KT * 16;
+    if (16 + 2 * (xb + wb) > LDS_LIMIT) return false;
+    g.xbytes = (int)xb;
+    g.wbytes = (int)wb;
+    if (lds_bytes(v, g) > LDS_LIMIT) return false;
+    if ((long long)g.row_blocks * g.img_blocks * g.k_blocks > 0x7fffffffLL) return false;
+    g.by_wo = fast_div(a.Wo);
+    g.by_w = fast_div(a.W);
+    g.by_upi = fast_div(g.UPI);
+    g.by_nb = fast_div(g.NB);
+    g.by_kblocks = fast_div(g.k_blocks);
+    g.by_rowblocks = fast_div(g.row_blocks);
+    *out = g;
+    return true;
+}
+
+// Relative time estimate in MFMA-clock cycles: rounds of blocks over the 256 CUs, each round costing
+// the busiest wave's MFMA time plus a fixed fill/drain overhead, plus the bytes staged through LDS
+// (halo and filter re-reads) at a nominal rate.
+double cost(const ConvArgs& a, const Variant& v, const IgemmGeom& g)
+{
+    const long long blocks = (long long)g.row_blocks * g.img_blocks * g.k_blocks;
+    const long long rounds = (blocks + 255) / 256;
+    const int used = (g.NB * g.TH * a.Wo + 31) / 32;
+    int per_wave = (used + v.WM - 1) / v.WM;
+    if (per_wave > v.TM) per_wave = v.TM;
+    const double mfma = 32.0 * per_wave * v.TN * (a.R * a.S) * (v.CC / 16) * g.n_stages;
+    const double overhead = 6000.0 + 1500.0 * g.n_stages;
+    const double staged = (double)blocks * g.n_stages * (g.xbytes + g.wbytes) / 256.0 / 64.0;   // 64 B/clk/CU
+    return (double)rounds * (mfma + overhead) + staged;
+}
+
+// Developer override: CVX_IGEMM_FORCE="<variant name>,<NB>,<TH>" pins the variant and tile shape.
+bool forced(const ConvArgs& a, const Variant** vout, IgemmGeom* gout)
+{
+    static const char* env = getenv("CVX_IGEMM_FORCE");
+    if (!env || !*env) return false;
+    char name[96];
+    int nb = 0, th = 0;
+    if (sscanf(env, "%95[^,],%d,%d", name, &nb, &th) != 3) return false;
+    for (int i = 0; i < kNumVariants; ++i) {
+        if (strcmp(name, kVariants[i].name) == 0 && plan(a, kVariants[i], nb, th, gout)) {
+            *vout = &kVariants[i];
+            return true;
+        }
+    }
+    return false;
+}
+
+bool choose(const ConvArgs& a, const Variant** vout, IgemmGeom* gout)
+{
+    if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
+    if (a.groups != 1) return false;
+    if (a.C < 8) return false;                                 // too few channels to fill an octet
+    const long long xbytes = (long long)a.N * a.C * a.H * a.W * 2, ybytes = (long long)a.N * a.K * a.Ho * a.Wo * 2;
+    if (xbytes >= (1LL << 31) || ybytes >= (1LL << 31)) return false;
+    if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y) & 15) return false;
+    if (forced(a, vout, gout)) return true;
+    double best = 1e300;
+    bool found = false;
+    const int HoWo = a.Ho * a.Wo;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant& v = kVariants[i];
+        const int PT = v.WM * v.TM * 32;
+        if (a.Wo > PT) continue;
+        const bool multi = HoWo <= PT;           // whole images fit: tile over images
+        const int hi = multi ? PT / HoWo : PT / a.Wo;
+        for (int t = hi; t >= 1; --t) {
+            IgemmGeom g;
+            if (!plan(a, v, multi ? t : 1, multi ? a.Ho : t, &g)) continue;
+            const double c = cost(a, v, g);
+            if (c < best) {
+                best = c;
+                *vout = &v;
+                *gout = g;
+                found = true;
+            }
+        }
+    }
+    return found;
+}
+
+}  // namespace
+
+#ifdef CVX_PHASE_TRACE
+extern "C" int cvx_debug_set_phase_trace(unsigned long long* device_buffer)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_phase_trace), &device_buffer, sizeof(device_buffer));
+}
+#endif
+
+bool igemm_supported(const ConvArgs& a, const char** variant_name)
+{
+    const Variant* v;
+    IgemmGeom g;
+    if (!choose(a, &v, &g)) return false;
+    if (variant_name) *variant_name = v->name;
+    return true;
+}
+
+hipError_t launch_igemm(const ConvArgs& a, hipStream_t s)
+{
+    const Variant* v;
+    IgemmGeom g;
+    if (!choose(a, &v, &g)) return hipErrorInvalidValue;
+    auto kern = a.dtype == DT_BF16 ? v->kern_bf16 : v->kern_f16;
+    const int lds = lds_bytes(*v, g);
+    // Raise the dynamic-LDS limit of each kernel once (the call is not a stream operation).
+    static bool raised[kNumVariants][2];
+    const int vi = (int)(v - kVariants), di = a.dtype == DT_BF16 ? 0 : 1;
+    if (!raised[vi][di]) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT);
+        if (e != hipSuccess) return e;
+        raised[vi][di] = true;
+    }
+    const dim3 grid((unsigned)(g.row_blocks * g.img_blocks * g.k_blocks)), block(v->WM * v->WN * 64);
+    hipLaunchKernelGGL(kern, grid, block, lds, s, a, g);
+    return hipGetLastError();
+}
+
+}  // namespace cvx
