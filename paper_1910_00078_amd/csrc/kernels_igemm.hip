@@ -38,15 +38,17 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 // 32 slots per block (16 wall-clock stamps, then 16 shader-clock stamps).
 #ifdef CVX_PHASE_TRACE
 __device__ unsigned long long* g_phase_trace = nullptr;
-#define CVX_TRACE_MARK(slot)                                                                      \
+#define CVX_TRACE_MARK(slot) CVX_TRACE_MARK_T(slot, 0)
+#define CVX_TRACE_MARK_T(slot, t)                                                                 \
     do {                                                                                          \
-        if (threadIdx.x == 0 && g_phase_trace) {                                                  \
+        if (threadIdx.x == (t) && g_phase_trace) {                                                  \
             g_phase_trace[(size_t)blockIdx.x * 32 + (slot)] = wall_clock64();                     \
             g_phase_trace[(size_t)blockIdx.x * 32 + 16 + (slot)] = clock64();                     \
         }                                                                                         \
     } while (0)
 #else
 #define CVX_TRACE_MARK(slot) do { } while (0)
+#define CVX_TRACE_MARK_T(slot, t) do { } while (0)
 #endif
 
 // Division of small non-negative integers by a runtime divisor chosen on the host: q = n / d for
@@ -60,9 +62,10 @@ struct IgemmGeom {
     int NB;          // images per pixel tile
     int TH;          // output rows per pixel tile (tiles span the full output width)
     int PH;          // input rows a tile needs: (TH-1)*stride_h + (R-1)*dil_h + 1
-    int WP;          // LDS row pitch in elements: W + 2*pad_w (the pad columns stay zero)
+    int WP;          // LDS row pitch in elements: W + 2*pad_w rounded up to a multiple of 8 (pad columns stay zero)
     int UPI;         // loader units (8 flat elements x 8 channels) per (octet, image)
-    int SLOTS;       // LDS elements per (octet, image) = PH * WP
+    int SLOTS;       // logical LDS elements per (octet, image) = PH * WP
+    int PSLOTS;      // physical ones: one spare 16-byte slot after every 8 (see lds_slot)
     int row_blocks, img_blocks, k_blocks;
     int n_stages;    // ceil(C / CC)
     int a_units;     // input loader units per stage
@@ -114,14 +117,32 @@ __device__ __forceinline__ uint32_t pack_halves(uint32_t a, int ha, uint32_t b, 
     return __builtin_amdgcn_perm(a, b, sel);
 }
 
+// Physical position of logical element `s` of an (octet, image) region.  The loader's lanes each
+// own 8 consecutive elements and write element e of all of them in one instruction, i.e. a lane
+// stride of 8 slots = 128 bytes, which would put 32 lanes on the same 4 LDS banks.  One spare slot
+// after every 8 makes that stride 9 slots, which walks through all bank groups; rows of 32
+// consecutive elements (what an MFMA fragment read touches) stay spread as well.  Because the row
+// pitch WP is a multiple of 8, moving by whole rows is still a constant byte offset (18 * WP).
+__device__ __forceinline__ int lds_slot(int s) { return s + (s >> 3); }
+
 // LDS map (bytes): two stage buffers from offset 16, each an input region (xbytes, whose last 16
 // bytes are a trash slot for loader writes that must not land in the image) followed by a filter
 // region (wbytes).  After the last stage the same memory holds the output tile for the store.
+//
+// The block is split by role.  The first WM*WN waves are consumers: they own the accumulators and
+// do nothing in the main loop but read fragments from LDS and issue MFMAs.  The next NPW waves are
+// producers: they fetch stage s+2 from device memory, and transpose and write stage s+1 into LDS,
+// while the consumers multiply stage s.  One consumer and one producer wave share each SIMD, so the
+// producers' vector-ALU and memory work runs in the shadow of the matrix pipe.  One s_barrier per
+// stage hands a finished buffer from producers to consumers and a drained one back.
 template <int DT, int WM, int WN, int TM, int TN, int CC, int TAPS, int UA, int UB>
-__global__ void __launch_bounds__(WM * WN * 64)
+__global__ void __launch_bounds__((WM * WN + 4) * 64)
 igemm_kernel(ConvArgs a, IgemmGeom g)
 {
-    constexpr int THREADS = WM * WN * 64;
+    constexpr int NCW = WM * WN;           // consumer waves
+    constexpr int NPW = 4;                 // producer waves
+    constexpr int THREADS = (NCW + NPW) * 64;
+    constexpr int PTHREADS = NPW * 64;
     constexpr int KT = WN * TN * 32;       // filters per block   (MFMA B operand / D columns)
     constexpr int PT = WM * TM * 32;       // pixels per block    (MFMA A operand / D rows)
     constexpr int OCT = CC / 8;
@@ -133,14 +154,10 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     CVX_TRACE_MARK(0);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
-    const int l32 = lane & 31, half = lane >> 5;
-    const int wm = wave / WN, wn = wave % WN;
+    const bool producer = wave >= NCW;
     const int taps = TAPS > 0 ? TAPS : a.R * a.S;
     const int HW = a.H * a.W, HoWo = a.Ho * a.Wo;
-    const long long x_total = (long long)a.N * a.C * HW;
-    const long long w_total = (long long)a.K * a.C * taps;
-    const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
-    const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
+    const int stage_bytes = g.xbytes + g.wbytes;
 
     // ---- which tile: consecutive logical ids stay on one XCD (hardware deals blocks round-robin
     //      over the 8 XCDs), and blocks that share an input tile (differing only in the filter
@@ -160,369 +177,450 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     const int rows = min(g.TH, a.Ho - p0);
     const int nimg = min(g.NB, a.N - n0);
     const int ppi = rows * a.Wo;                       // output pixels per image in this tile
-    const int h_lo = p0 * a.stride_h - a.pad_h;        // first input row of the patch (may be < 0)
-    const int e_lo = h_lo * a.W;                       // flat element index of the patch start
-    const int n_ptiles = (nimg * ppi + 31) >> 5;       // pixel tiles holding at least one pixel
+    const int npix = nimg * ppi;
+    const int n_ptiles = (npix + 31) >> 5;             // pixel tiles holding at least one pixel
 
-    // ---- loader bookkeeping, part 1: what each thread fetches (needed before the first loads).
-    //      An input unit is 8 consecutive flat (h,w) elements of the patch for the 8 channels of
-    //      one octet.  A filter unit is (filter, octet): 8 channels x TAPS taps, contiguous in memory.
-    long long a_goff[UA];
-    int a_oct[UA], a_img[UA], a_ui[UA];
-#pragma unroll
-    for (int u = 0; u < UA; ++u) {
-        const int ua = tid + u * THREADS;
-        a_oct[u] = -1;
-        a_goff[u] = 0;
-        a_img[u] = 0;
-        a_ui[u] = 0;
-        if (ua < g.a_units) {
-            const int t = g.by_upi.div(ua);
-            const int ui = ua - t * g.UPI;
-            const int oct = g.by_nb.div(t);
-            const int img = t - oct * g.NB;
-            a_oct[u] = oct;
-            a_img[u] = img;
-            a_ui[u] = ui;
-            a_goff[u] = ((long long)(n0 + img) * a.C + oct * 8) * HW + e_lo + ui * 8;
-        }
-    }
-    constexpr int BROWS = TAPS > 0 ? (8 * TAPS * 2 + 15) / 16 : 1;   // 16-byte loads per filter unit
-    int b_k[UB], b_oct[UB];
-#pragma unroll
-    for (int u = 0; u < UB; ++u) {
-        const int ub = tid + u * THREADS;
-        b_k[u] = ub % KT;
-        b_oct[u] = ub / KT;
-        if (ub >= g.b_units) b_oct[u] = -1;
-    }
+    if (producer) {
+        // =========================================================================================
+        // producer waves
+        // =========================================================================================
+        const int ptid = tid - NCW * 64;
+        const long long x_total = (long long)a.N * a.C * HW;
+        const long long w_total = (long long)a.K * a.C * taps;
+        const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
+        const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
+        const int h_lo = p0 * a.stride_h - a.pad_h;    // first input row of the patch (may be < 0)
+        const int e_lo = h_lo * a.W;                   // flat element index of the patch start
 
-    u32x4 ra[UA][8];
-    u32x4 rbv[UB][BROWS];
-
-    // Global loads only; nothing here consumes a loaded value, so all of a stage's loads are in
-    // flight together and are first waited on in store_stage.
-    auto load_stage = [&](int st) {
-        const int cbase = st * CC;
+        // What each thread fetches.  An input unit is 8 consecutive flat (h,w) elements of the patch
+        // for the 8 channels of one octet.  A filter unit is (filter, octet): 8 channels x TAPS taps,
+        // contiguous in memory.
+        long long a_goff[UA];
+        int a_oct[UA], a_img[UA], a_ui[UA];
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
-            if (a_oct[u] >= 0) {
-                const int c0 = cbase + a_oct[u] * 8;
-                const long long off0 = a_goff[u] + (long long)cbase * HW;
-                const bool fast = off0 >= 0 && off0 + 7LL * HW + 8 <= x_total && c0 + 8 <= a.C;
-                if (fast) {
+            const int ua = ptid + u * PTHREADS;
+            a_oct[u] = -1;
+            a_goff[u] = 0;
+            a_img[u] = 0;
+            a_ui[u] = 0;
+            if (ua < g.a_units) {
+                const int t = g.by_upi.div(ua);
+                const int ui = ua - t * g.UPI;
+                const int oct = g.by_nb.div(t);
+                const int img = t - oct * g.NB;
+                a_img[u] = img;
+                a_ui[u] = ui;
+                a_goff[u] = ((long long)(n0 + img) * a.C + oct * 8) * HW + e_lo + ui * 8;
+                if (img < nimg) a_oct[u] = oct;        // images past N: nothing to fetch, LDS stays zero
+            }
+        }
+        constexpr int BROWS = TAPS > 0 ? (8 * TAPS * 2 + 15) / 16 : 1;   // 16-byte loads per filter unit
+        int b_k[UB], b_oct[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int ub = ptid + u * PTHREADS;
+            b_k[u] = ub % KT;
+            b_oct[u] = ub / KT;
+            if (ub >= g.b_units) b_oct[u] = -1;
+        }
+
+        // Two register sets: the loads of two stages are in flight at once, so a stage's data has
+        // two stage times to arrive from device memory.
+        struct StageRegs {
+            u32x4 ra[UA][8];
+            u32x4 rbv[UB][BROWS];
+        };
+        StageRegs R0, R1;
+
+        // Global loads only; nothing here consumes a loaded value, so all of a stage's loads are in
+        // flight together and are first waited on in store_stage.
+        auto load_stage = [&](int st, StageRegs& R) {
+            auto& ra = R.ra;
+            auto& rbv = R.rbv;
+            const int cbase = st * CC;
+#pragma unroll
+            for (int u = 0; u < UA; ++u) {
+                if (a_oct[u] >= 0) {
+                    const int c0 = cbase + a_oct[u] * 8;
+                    const long long off0 = a_goff[u] + (long long)cbase * HW;
+                    const bool fast = off0 >= 0 && off0 + 7LL * HW + 8 <= x_total && c0 + 8 <= a.C;
+                    if (fast) {
 #ifdef CVX_EXP_NO_XLOAD
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) ra[u][j] = u32x4{(uint32_t)j, 0u, 0u, 0u};
+                        for (int j = 0; j < 8; ++j) ra[u][j] = u32x4{(uint32_t)j, 0u, 0u, 0u};
 #else
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) ra[u][j] = *(const u32x4_a2*)(xg + off0 + (long long)j * HW);
+                        for (int j = 0; j < 8; ++j) ra[u][j] = *(const u32x4_a2*)(xg + off0 + (long long)j * HW);
 #endif
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        u32x4 v = {0u, 0u, 0u, 0u};
-                        if (c0 + j < a.C) v = load8(xg, off0 + (long long)j * HW, x_total);
-                        ra[u][j] = v;
-                    }
-                }
-            }
-        }
-        if constexpr (TAPS > 0) {
-#pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                if (b_oct[u] >= 0) {
-                    const int k = k0 + b_k[u];
-                    const int c0 = cbase + b_oct[u] * 8;
-                    const long long off0 = ((long long)k * a.C + c0) * TAPS;
-                    const bool full = k < a.K && c0 + 8 <= a.C;
-                    if (full) {
-#pragma unroll
-                        for (int i = 0; i < BROWS; ++i) {
-#ifdef CVX_EXP_NO_WLOAD
-                            rbv[u][i] = u32x4{(uint32_t)i, 0u, 0u, 0u};
-                            continue;
-#endif
-                            if (i * 8 + 8 <= 8 * TAPS) rbv[u][i] = *(const u32x4_a2*)(wg + off0 + i * 8);
-                            else rbv[u][i] = load8(wg, off0 + i * 8, w_total);
-                        }
                     } else {
-                        // ragged: filters past K or channels past C contribute zeros
 #pragma unroll
-                        for (int i = 0; i < BROWS; ++i) {
+                        for (int j = 0; j < 8; ++j) {
                             u32x4 v = {0u, 0u, 0u, 0u};
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                const int t = i * 8 + e;          // = j * TAPS + tap
-                                const int j = t / TAPS;
-                                if (k < a.K && j < 8 && c0 + j < a.C)
-                                    v[e >> 1] |= ((uint32_t)wg[off0 + t]) << ((e & 1) * 16);
-                            }
-                            rbv[u][i] = v;
+                            if (c0 + j < a.C) v = load8(xg, off0 + (long long)j * HW, x_total);
+                            ra[u][j] = v;
                         }
                     }
                 }
             }
-        }
-    };
-
-    CVX_TRACE_MARK(1);
-    load_stage(0);
-
-    // ---- everything below up to the first barrier overlaps the latency of those loads --------
-
-    // loader bookkeeping, part 2: a_dst holds the LDS byte offset (inside the input region) that
-    // each of a unit's 8 elements goes to; elements outside the image go to the trash slot.
-    int a_dst[UA][8];
+            if constexpr (TAPS > 0) {
 #pragma unroll
-    for (int u = 0; u < UA; ++u) {
+                for (int u = 0; u < UB; ++u) {
+                    if (b_oct[u] >= 0) {
+                        const int k = k0 + b_k[u];
+                        const int c0 = cbase + b_oct[u] * 8;
+                        const long long off0 = ((long long)k * a.C + c0) * TAPS;
+                        const bool full = k < a.K && c0 + 8 <= a.C;
+                        if (full) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) a_dst[u][e] = g.xbytes - 16;
-        if (a_oct[u] >= 0) {
-            const int rel0 = a_ui[u] * 8;
-            int row = g.by_w.div(rel0);
-            int col = rel0 - row * a.W;
-            const int base = (a_oct[u] * g.NB + a_img[u]) * g.SLOTS + a.pad_w;
+                            for (int i = 0; i < BROWS; ++i) {
+#ifdef CVX_EXP_NO_WLOAD
+                                rbv[u][i] = u32x4{(uint32_t)i, 0u, 0u, 0u};
+                                continue;
+#endif
+                                if (i * 8 + 8 <= 8 * TAPS) rbv[u][i] = *(const u32x4_a2*)(wg + off0 + i * 8);
+                                else rbv[u][i] = load8(wg, off0 + i * 8, w_total);
+                            }
+                        } else {
+                            // ragged: filters past K or channels past C contribute zeros
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int eabs = e_lo + rel0 + e;
-                if (a_img[u] < nimg && eabs >= 0 && eabs < HW && row < g.PH)
-                    a_dst[u][e] = (base + row * g.WP + col) * 16;
-                if (++col == a.W) { col = 0; ++row; }
+                            for (int i = 0; i < BROWS; ++i) {
+                                u32x4 v = {0u, 0u, 0u, 0u};
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) {
+                                    const int t = i * 8 + e;          // = j * TAPS + tap
+                                    const int j = t / TAPS;
+                                    if (k < a.K && j < 8 && c0 + j < a.C)
+                                        v[e >> 1] |= ((uint32_t)wg[off0 + t]) << ((e & 1) * 16);
+                                }
+                                rbv[u][i] = v;
+                            }
+                        }
+                    }
+                }
             }
-        }
-    }
+        };
 
-    CVX_TRACE_MARK(9);
-    // per-lane LDS byte offset of tap (0,0), octet `half`, for each of the wave's pixel tiles
-    const int oct_bytes = g.NB * g.SLOTS * 16;
-    int xbase[TM];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        const int f = (wm * TM + tm) * 32 + l32;
-        int img = 0, rem = f;
-        if (g.NB > 1) {                 // multi-image tiles hold whole images: ppi = Ho * Wo
-            img = f / ppi;
-            rem = f - img * ppi;
-        }
-        const int py = g.by_wo.div(rem);
-        const int px = rem - py * a.Wo;
-        const bool valid = f < nimg * ppi;
-        xbase[tm] = (valid ? (img * g.SLOTS + py * a.stride_h * g.WP + px * a.stride_w) * 16 : 0) + half * oct_bytes;
-    }
-    const int b_lane = ((wn * TN) * 32 + l32 + half * KT) * 16;
-    const bool wave_on = (wm * TM) < n_ptiles;         // this wave owns at least one live pixel tile
+        load_stage(0, R0);
+        if (g.n_stages > 1) load_stage(1, R1);
 
-    CVX_TRACE_MARK(10);
-    // epilogue constants of this lane's filters; without batch-norm the bias seeds the accumulators
-    const bool has_bn = a.bn_scale != nullptr;
-    ChannelAffine ca[TN];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(k0 + (wn * TN + tn) * 32 + l32, a.K - 1));
-
-    CVX_TRACE_MARK(11);
-    {
-        // zero both input regions: pad columns and rows outside the image are never written
-        // afterwards, so they stay zero for every stage
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int i = tid * 16; i < g.xbytes; i += THREADS * 16) {
-            *(u32x4*)(smem + BUF0 + i) = z;
-            *(u32x4*)(smem + BUF0 + g.xbytes + g.wbytes + i) = z;
-        }
-    }
-
-    auto store_stage = [&](int st, int buf) {
-        unsigned char* xs = smem + BUF0 + buf * (g.xbytes + g.wbytes);
-        unsigned char* ws = xs + g.xbytes;
+        // a_dst: the LDS byte offset (inside the input region) each of a unit's 8 elements goes to;
+        // elements outside the image go to the region's trash slot.
+        int a_dst[UA][8];
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a_dst[u][e] = g.xbytes - 16;
             if (a_oct[u] >= 0) {
-                // 8 channel rows x 8 elements  ->  8 elements x 8 channels
+                const int rel0 = a_ui[u] * 8;
+                int row = g.by_w.div(rel0);
+                int col = rel0 - row * a.W;
+                const int region = (a_oct[u] * g.NB + a_img[u]) * g.PSLOTS;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    u32x4 o;
-#pragma unroll
-                    for (int m = 0; m < 4; ++m)
-                        o[m] = pack_halves(ra[u][2 * m + 1][e >> 1], e & 1, ra[u][2 * m][e >> 1], e & 1);
-                    *(u32x4*)(xs + a_dst[u][e]) = o;
+                    const int eabs = e_lo + rel0 + e;
+                    if (a_img[u] < nimg && eabs >= 0 && eabs < HW && row < g.PH)
+                        a_dst[u][e] = (region + lds_slot(row * g.WP + col + a.pad_w)) * 16;
+                    if (++col == a.W) { col = 0; ++row; }
                 }
             }
         }
-        if constexpr (TAPS > 0) {
+        {
+            // zero both input regions: pad columns and rows outside the image are never written
+            // afterwards, so they stay zero for every stage
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            for (int i = ptid * 16; i < g.xbytes; i += PTHREADS * 16) {
+                *(u32x4*)(smem + BUF0 + i) = z;
+                *(u32x4*)(smem + BUF0 + stage_bytes + i) = z;
+            }
+        }
+
+        auto store_stage = [&](int st, int buf, const StageRegs& R) {
+            auto& ra = R.ra;
+            auto& rbv = R.rbv;
+            unsigned char* xs = smem + BUF0 + buf * stage_bytes;
+            unsigned char* ws = xs + g.xbytes;
 #pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                if (b_oct[u] >= 0) {
+            for (int u = 0; u < UA; ++u) {
+                if (a_oct[u] >= 0) {
+                    // 8 channel rows x 8 elements  ->  8 elements x 8 channels
 #pragma unroll
-                    for (int tap = 0; tap < TAPS; ++tap) {
+                    for (int e = 0; e < 8; ++e) {
                         u32x4 o;
 #pragma unroll
-                        for (int m = 0; m < 4; ++m) {
-                            const int t0 = (2 * m) * TAPS + tap, t1 = (2 * m + 1) * TAPS + tap;
-                            o[m] = pack_halves(rbv[u][t1 >> 3][(t1 >> 1) & 3], t1 & 1,
-                                               rbv[u][t0 >> 3][(t0 >> 1) & 3], t0 & 1);
-                        }
-                        *(u32x4*)(ws + ((tap * OCT + b_oct[u]) * KT + b_k[u]) * 16) = o;
+                        for (int m = 0; m < 4; ++m)
+                            o[m] = pack_halves(ra[u][2 * m + 1][e >> 1], e & 1, ra[u][2 * m][e >> 1], e & 1);
+                        *(u32x4*)(xs + a_dst[u][e]) = o;
                     }
                 }
             }
-        } else {
-            // any filter size: element-wise gather from global memory, scatter into LDS
-            const int cbase = st * CC;
-            for (int pi = tid; pi < KT * CC; pi += THREADS) {
-                const int cl = pi % CC, kl = pi / CC;
-                const int k = k0 + kl, c = cbase + cl;
-                const bool ok = k < a.K && c < a.C;
-                const long long off0 = ((long long)k * a.C + c) * taps;
-                for (int t = 0; t < taps; ++t) {
-                    const uint16_t v = ok ? wg[off0 + t] : (uint16_t)0;
-                    *(uint16_t*)(ws + ((t * OCT + (cl >> 3)) * KT + kl) * 16 + (cl & 7) * 2) = v;
+            if constexpr (TAPS > 0) {
+#pragma unroll
+                for (int u = 0; u < UB; ++u) {
+                    if (b_oct[u] >= 0) {
+#pragma unroll
+                        for (int tap = 0; tap < TAPS; ++tap) {
+                            u32x4 o;
+#pragma unroll
+                            for (int m = 0; m < 4; ++m) {
+                                const int t0 = (2 * m) * TAPS + tap, t1 = (2 * m + 1) * TAPS + tap;
+                                o[m] = pack_halves(rbv[u][t1 >> 3][(t1 >> 1) & 3], t1 & 1,
+                                                   rbv[u][t0 >> 3][(t0 >> 1) & 3], t0 & 1);
+                            }
+                            *(u32x4*)(ws + ((tap * OCT + b_oct[u]) * KT + b_k[u]) * 16) = o;
+                        }
+                    }
+                }
+            } else {
+                // any filter size: element-wise gather from global memory, scatter into LDS
+                const int cbase = st * CC;
+                for (int pi = ptid; pi < KT * CC; pi += PTHREADS) {
+                    const int cl = pi % CC, kl = pi / CC;
+                    const int k = k0 + kl, c = cbase + cl;
+                    const bool ok = k < a.K && c < a.C;
+                    const long long off0 = ((long long)k * a.C + c) * taps;
+                    for (int t = 0; t < taps; ++t) {
+                        const uint16_t v = ok ? wg[off0 + t] : (uint16_t)0;
+                        *(uint16_t*)(ws + ((t * OCT + (cl >> 3)) * KT + kl) * 16 + (cl & 7) * 2) = v;
+                    }
                 }
             }
-        }
-    };
+        };
 
-    f32x16 acc[TM][TN];
+        __syncthreads();                               // (A) zero fill complete
+        store_stage(0, 0, R0);
+        if (g.n_stages > 2) load_stage(2, R0);
+        __syncthreads();                               // (B) stage 0 is in LDS
+        CVX_TRACE_MARK_T(2, NCW * 64);
+        // Each pass hands the consumers one stage: while they multiply stage st, stage st+1 is
+        // transposed into the other LDS buffer (this waits for its loads) and the loads of stage
+        // st+3 take over the registers just freed.  Unrolled by two so the register sets alternate
+        // at compile time.
+        for (int st = 0; st < g.n_stages; st += 2) {
+            if (st + 1 < g.n_stages) {
+                store_stage(st + 1, 1, R1);
+                if (st + 3 < g.n_stages) load_stage(st + 3, R1);
+            }
+            if (st < 6) CVX_TRACE_MARK_T(4 + 2 * st, NCW * 64);
+            __syncthreads();                           // stage st consumed, stage st+1 in LDS
+            if (st + 1 < g.n_stages) {
+                if (st + 2 < g.n_stages) {
+                    store_stage(st + 2, 0, R0);
+                    if (st + 4 < g.n_stages) load_stage(st + 4, R0);
+                }
+                if (st + 1 < 6) CVX_TRACE_MARK_T(4 + 2 * (st + 1), NCW * 64);
+                __syncthreads();                       // stage st+1 consumed, stage st+2 in LDS
+            }
+        }
+    } else {
+        // =========================================================================================
+        // consumer waves
+        // =========================================================================================
+        const int l32 = lane & 31, half = lane >> 5;
+        const int wm = wave / WN, wn = wave % WN;
+
+        // Per-lane LDS byte offsets for each of the wave's pixel tiles: xb[tm][s] addresses filter
+        // column s of filter row 0 (octet `half`); further filter rows are a constant row_bytes away.
+        // Kernels built for a fixed filter size keep one offset per filter column; the others keep the
+        // logical element index and derive the address per tap.
+        constexpr int NSW = TAPS == 9 ? 3 : 1;
+        const int oct_bytes = g.NB * g.PSLOTS * 16;
+        const int row_bytes = a.dil_h * g.WP * 18;                 // one filter row down, in bytes
+        int xb[TM][NSW];
+        int xl[TM], xr[TM];                                        // logical element, region byte offset
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+        for (int tm = 0; tm < TM; ++tm) {
+            const int f = (tm * WM + wm) * 32 + l32;      // pixel tiles are dealt round-robin to the wave rows
+            int img = 0, rem = f;
+            if (g.NB > 1) {                 // multi-image tiles hold whole images: ppi = Ho * Wo
+                img = f / ppi;
+                rem = f - img * ppi;
+            }
+            const int py = g.by_wo.div(rem);
+            const int px = rem - py * a.Wo;
+            const bool valid = f < npix;
+            xl[tm] = valid ? py * a.stride_h * g.WP + px * a.stride_w : 0;
+            xr[tm] = (valid ? img * g.PSLOTS * 16 : 0) + half * oct_bytes;
+#pragma unroll
+            for (int sw = 0; sw < NSW; ++sw) xb[tm][sw] = xr[tm] + lds_slot(xl[tm] + sw * a.dil_w) * 16;
+        }
+        const int b_lane = ((wn * TN) * 32 + l32 + half * KT) * 16;
+        const bool wave_on = wm < n_ptiles;            // this wave owns at least one live pixel tile
+
+        // epilogue constants of this lane's filters: only the loads are issued here; they are turned
+        // into (mul, add) after the prologue barriers, when they have long arrived
+        const bool has_bn = a.bn_scale != nullptr;
+        uint32_t bias_raw[TN];
+        float bn_raw[TN][4];
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            const float seed = has_bn ? 0.0f : ca[tn].add;
+            const int k = min(k0 + (wn * TN + tn) * 32 + l32, a.K - 1);
+            bias_raw[tn] = 0u;
+            if (a.bias) bias_raw[tn] = a.bias_f32 ? ((const uint32_t*)a.bias)[k] : (uint32_t)((const uint16_t*)a.bias)[k];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
+            for (int j = 0; j < 4; ++j) bn_raw[tn][j] = 0.0f;
+            if (has_bn) {
+                bn_raw[tn][0] = a.bn_scale[k];
+                bn_raw[tn][1] = a.bn_shift[k];
+                bn_raw[tn][2] = a.bn_mean[k];
+                bn_raw[tn][3] = a.bn_var[k];
+            }
         }
+        ChannelAffine ca[TN];
 
-    // One k-step = one filter tap x 16 channels: TM pixel fragments (MFMA A operand), TN filter
-    // fragments (B operand), TM*TN MFMAs.  The instruction order is pinned: after each of the first
-    // TM+TN MFMAs of a step, one fragment of the NEXT step is read (filters first, then pixels in
-    // the order the MFMAs will want them), so LDS latency hides behind the matrix pipe and the
-    // waits the compiler inserts are partial.
-    auto compute_stage = [&](int buf) {
-        if (!wave_on) return;
-        const unsigned char* xs = smem + BUF0 + buf * (g.xbytes + g.wbytes);
-        const unsigned char* ws = xs + g.xbytes + b_lane;
-        if constexpr (TAPS == 9 || TAPS == 1) {
-            constexpr int NS = TAPS * KSTEPS;
-            const int S3 = TAPS == 9 ? a.S : 1;
-            auto tap_bytes = [&](int tap) {
-                const int r = TAPS == 9 ? (S3 == 3 ? tap / 3 : tap / S3) : 0;
-                const int s = tap - r * S3;
-                return (r * a.dil_h * g.WP + s * a.dil_w) * 16;
-            };
-            u32x4 fa[2][TM], fb[2][TN];
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(ws + tn * 32 * 16);
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) fa[0][tm] = *(const u32x4*)(xs + xbase[tm]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < NS; ++i) {
-                const int b = i & 1, nb = b ^ 1;
-                const bool more = i + 1 < NS;
-                const int ntap = (i + 1) / KSTEPS, nkk = (i + 1) % KSTEPS;
-                const int xo = more ? 2 * nkk * oct_bytes + tap_bytes(ntap) : 0;
-                int issued = 0;
-                auto read_next = [&]() {
-                    if (issued < TN) fb[nb][issued] = *(const u32x4*)(ws + ((ntap * OCT + 2 * nkk) * KT + issued * 32) * 16);
-                    else fa[nb][issued - TN] = *(const u32x4*)(xs + xbase[issued - TN] + xo);
-                    ++issued;
+        f32x16 acc[TM][TN];
+
+        // One k-step = one filter tap x 16 channels: TM pixel fragments (MFMA A operand), TN filter
+        // fragments (B operand), TM*TN MFMAs.  The instruction order is pinned: after each of the
+        // first TM+TN MFMAs of a step, one fragment of the NEXT step is read (filters first, then
+        // pixels in the order the MFMAs will want them), so LDS latency hides behind the matrix pipe
+        // and the waits the compiler inserts are partial.
+        auto compute_stage = [&](int buf) {
+            if (!wave_on) return;
+#ifdef CVX_EXP_NO_MFMA
+            return;
+#endif
+            const unsigned char* xs = smem + BUF0 + buf * stage_bytes;
+            const unsigned char* ws = xs + g.xbytes + b_lane;
+            if constexpr (TAPS == 9 || TAPS == 1) {
+                constexpr int NS = TAPS * KSTEPS;
+                auto tap_addr = [&](int tm, int tap) {            // tap is a compile-time constant here
+                    return xb[tm][TAPS == 9 ? tap % 3 : 0] + (TAPS == 9 ? tap / 3 : 0) * row_bytes;
                 };
+                u32x4 fa[2][TM], fb[2][TN];
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm) {
+                for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(ws + tn * 32 * 16);
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) {
-                        acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
-                        __builtin_amdgcn_sched_barrier(0);
+                for (int tm = 0; tm < TM; ++tm) fa[0][tm] = *(const u32x4*)(xs + tap_addr(tm, 0));
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < NS; ++i) {
+                    const int b = i & 1, nb = b ^ 1;
+                    const bool more = i + 1 < NS;
+                    const int ntap = (i + 1) / KSTEPS, nkk = (i + 1) % KSTEPS;
+                    const int xo = 2 * nkk * oct_bytes;
+                    int issued = 0;
+                    auto read_next = [&]() {
+                        if (issued < TN) fb[nb][issued] = *(const u32x4*)(ws + ((ntap * OCT + 2 * nkk) * KT + issued * 32) * 16);
+                        else fa[nb][issued - TN] = *(const u32x4*)(xs + tap_addr(issued - TN, ntap) + xo);
+                        ++issued;
+                    };
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) {
+                            acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (more && issued < TM + TN) {
+                                read_next();
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < TM + TN; ++j) {
                         if (more && issued < TM + TN) {
                             read_next();
                             __builtin_amdgcn_sched_barrier(0);
                         }
                     }
                 }
+            } else {
+                int r = 0, s = 0;
+                for (int tap = 0; tap < taps; ++tap) {
+                    int ta[TM];
 #pragma unroll
-                for (int j = 0; j < TM + TN; ++j) {
-                    if (more && issued < TM + TN) {
-                        read_next();
-                        __builtin_amdgcn_sched_barrier(0);
+                    for (int tm = 0; tm < TM; ++tm) ta[tm] = xr[tm] + lds_slot(xl[tm] + s * a.dil_w) * 16 + r * row_bytes;
+#pragma unroll
+                    for (int kk = 0; kk < KSTEPS; ++kk) {
+                        u32x4 fa[TM], fb[TN];
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) fb[tn] = *(const u32x4*)(ws + ((tap * OCT + 2 * kk) * KT + tn * 32) * 16);
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm) fa[tm] = *(const u32x4*)(xs + ta[tm] + 2 * kk * oct_bytes);
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma_32x32x16<DT>(fa[tm], fb[tn], acc[tm][tn]);
                     }
-                }
-            }
-        } else {
-            int r = 0, s = 0;
-            for (int tap = 0; tap < taps; ++tap) {
-                const int tap_off = (r * a.dil_h * g.WP + s * a.dil_w) * 16;
-#pragma unroll
-                for (int kk = 0; kk < KSTEPS; ++kk) {
-                    u32x4 fa[TM], fb[TN];
-#pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) fb[tn] = *(const u32x4*)(ws + ((tap * OCT + 2 * kk) * KT + tn * 32) * 16);
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) fa[tm] = *(const u32x4*)(xs + xbase[tm] + 2 * kk * oct_bytes + tap_off);
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma_32x32x16<DT>(fa[tm], fb[tn], acc[tm][tn]);
-                }
-                if (++s == a.S) { s = 0; ++r; }
-            }
-        }
-    };
-
-    // ---- main pipeline
-    CVX_TRACE_MARK(12);
-    __syncthreads();
-    CVX_TRACE_MARK(13);
-    store_stage(0, 0);
-    CVX_TRACE_MARK(14);
-    __syncthreads();
-    CVX_TRACE_MARK(2);
-    for (int st = 0; st < g.n_stages; ++st) {
-        const int buf = st & 1;
-        const bool more = st + 1 < g.n_stages;
-        if (more) load_stage(st + 1);
-        compute_stage(buf);
-        if (st < 6) CVX_TRACE_MARK(3 + 2 * st);
-        if (more) store_stage(st + 1, buf ^ 1);
-        __syncthreads();
-        if (st < 6) CVX_TRACE_MARK(4 + 2 * st);
-    }
-
-    // ---- epilogue: batch-norm / activation on the accumulators in registers, one rounding to the
-    //      output type, then the tile goes through LDS as [filter][pixel] so that the single store
-    //      to device memory is 16 bytes per lane along the pixel axis.
-    uint16_t* ot = (uint16_t*)(smem + BUF0);
-    if (wave_on) {
-        auto stage_out = [&](auto&& act_fn) {
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int kl = (wn * TN + tn) * 32 + l32;
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        float v[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float t = acc[tm][tn][4 * q4 + j];
-                            v[j] = act_fn(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t);
-                        }
-                        const int f = (wm * TM + tm) * 32 + 8 * q4 + 4 * half;
-                        *(uint2*)(ot + kl * PTP + f) = make_uint2(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]));
-                    }
+                    if (++s == a.S) { s = 0; ++r; }
                 }
             }
         };
-        if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
-        else if (a.act == ACT_IDENTITY) stage_out([](float t) { return t; });
-        else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
+
+        CVX_TRACE_MARK(1);
+        __syncthreads();                               // (A)
+        __syncthreads();                               // (B) stage 0 is in LDS
+        // the bias loads issued above have had the whole prologue to arrive; without batch-norm the
+        // bias seeds the accumulators
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            float b = 0.0f;
+            if (a.bias) b = a.bias_f32 ? __uint_as_float(bias_raw[tn]) : bits16_to_f32<DT>((uint16_t)bias_raw[tn]);
+            if (has_bn) {
+                const float m = bn_raw[tn][0] / sqrtf(bn_raw[tn][3] + a.bn_eps);
+                ca[tn].mul = m;
+                ca[tn].add = (b - bn_raw[tn][2]) * m + bn_raw[tn][1];
+            } else {
+                ca[tn].mul = 1.0f;
+                ca[tn].add = b;
+            }
+        }
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const float seed = has_bn ? 0.0f : ca[tn].add;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
+            }
+        for (int st = 0; st < g.n_stages; ++st) {
+            compute_stage(st & 1);
+            if (st < 6) CVX_TRACE_MARK(3 + 2 * st);
+            __syncthreads();
+        }
+        CVX_TRACE_MARK(14);
+
+        // ---- epilogue, part 1: batch-norm / activation on the accumulators in registers, one
+        //      rounding to the output type, then the tile goes into LDS as [filter][pixel].
+        uint16_t* ot = (uint16_t*)(smem + BUF0);
+        if (wave_on) {
+            auto stage_out = [&](auto&& act_fn) {
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int kl = (wn * TN + tn) * 32 + l32;
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            float v[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const float t = acc[tm][tn][4 * q4 + j];
+                                v[j] = act_fn(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t);
+                            }
+                            const int f = (tm * WM + wm) * 32 + 8 * q4 + 4 * half;
+                            *(uint2*)(ot + kl * PTP + f) = make_uint2(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]));
+                        }
+                    }
+                }
+            };
+            if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
+            else if (a.act == ACT_IDENTITY) stage_out([](float t) { return t; });
+            else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
+        }
     }
-    __syncthreads();
+    __syncthreads();                                   // output tile complete in LDS
+
+    // ---- epilogue, part 2 (all waves): the single store to device memory, 16 bytes per lane along
+    //      the pixel axis.
     {
+        const uint16_t* ot = (const uint16_t*)(smem + BUF0);
         constexpr int CH = PT / 8;                 // 8-pixel chunks per filter row
         constexpr int RSTEP = THREADS / CH;        // filter rows covered per pass
-        constexpr int NPASS = KT / RSTEP;
+        constexpr int NPASS = (KT + RSTEP - 1) / RSTEP;
         const int chunk = tid % CH, row0 = tid / CH;
         const int f0 = chunk * 8;
-        const int npix = nimg * ppi;
         if (f0 < npix) {
             int img = 0, rem = f0;
             if (g.NB > 1) {
@@ -536,11 +634,14 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             for (int p = 0; p < NPASS; p += GRP) {
                 u32x4 v[GRP];
 #pragma unroll
-                for (int j = 0; j < GRP; ++j) v[j] = *(const u32x4*)(ot + (row0 + (p + j) * RSTEP) * PTP + f0);
+                for (int j = 0; j < GRP; ++j) {
+                    const int kl = min(row0 + (p + j) * RSTEP, KT - 1);
+                    v[j] = *(const u32x4*)(ot + kl * PTP + f0);
+                }
 #pragma unroll
                 for (int j = 0; j < GRP; ++j) {
                     const int kl = row0 + (p + j) * RSTEP;
-                    if (k0 + kl < a.K) {
+                    if (kl < KT && k0 + kl < a.K) {
                         uint16_t* dst = yg + obase + (size_t)kl * HoWo;
                         if (whole) {
                             *(u32x4_a2*)dst = v[j];
@@ -593,9 +694,12 @@ const Variant kVariants[] = {
     IGEMM_VARIANT("igemm_256x64_c32_3x3", 4, 1, 2, 2, 32, 9, 1, 1),
     IGEMM_VARIANT("igemm_256x64_c16_3x3", 4, 1, 2, 2, 16, 9, 1, 1),
     IGEMM_VARIANT("igemm_256x64_c16_3x3_u2", 4, 1, 2, 2, 16, 9, 2, 1),
+    IGEMM_VARIANT("igemm_128x128_c32_3x3", 2, 2, 2, 2, 32, 9, 1, 2),
     IGEMM_VARIANT("igemm_512x64_c32_1x1", 4, 1, 4, 2, 32, 1, 1, 1),
+    IGEMM_VARIANT("igemm_512x64_c64_1x1", 4, 1, 4, 2, 64, 1, 2, 2),
     IGEMM_VARIANT("igemm_256x64_c32_1x1", 4, 1, 2, 2, 32, 1, 1, 1),
-    IGEMM_VARIANT("igemm_256x64_c32_1x1_u2", 4, 1, 2, 2, 32, 1, 2, 1),
+    IGEMM_VARIANT("igemm_256x64_c64_1x1", 4, 1, 2, 2, 64, 1, 1, 2),
+    IGEMM_VARIANT("igemm_128x128_c64_1x1", 2, 2, 2, 2, 64, 1, 1, 4),
     IGEMM_VARIANT("igemm_256x64_c16_any", 4, 1, 2, 2, 16, 0, 2, 1),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
@@ -622,7 +726,8 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
 {
     const int taps = a.R * a.S;
     if (v.TAPS > 0 && v.TAPS != taps) return false;
-    const int threads = v.WM * v.WN * 64;
+    if (v.TAPS == 9 && (a.R != 3 || a.S != 3)) return false;      // the 9-tap kernels index taps as 3 x 3
+    const int threads = 4 * 64;                    // producer threads
     const int KT = v.WN * v.TN * 32, PT = v.WM * v.TM * 32, OCT = v.CC / 8;
     if (NB < 1 || TH < 1 || NB > a.N || TH > a.Ho) return false;
     if (NB > 1 && TH != a.Ho) return false;
@@ -632,12 +737,13 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     g.NB = NB;
     g.TH = TH;
     g.PH = (g.TH - 1) * a.stride_h + (a.R - 1) * a.dil_h + 1;
-    g.WP = a.W + 2 * a.pad_w;
+    g.WP = (a.W + 2 * a.pad_w + 7) & ~7;
     const long long slots = (long long)g.PH * g.WP;
     const long long upi = ((long long)g.PH * a.W + 7) / 8;
     if (slots > 65535 || upi > 65535) return false;
     g.UPI = (int)upi;
     g.SLOTS = (int)slots;
+    g.PSLOTS = g.SLOTS + g.SLOTS / 8 + 1;
     g.row_blocks = (a.Ho + g.TH - 1) / g.TH;
     g.img_blocks = (a.N + g.NB - 1) / g.NB;
     g.k_blocks = (a.K + KT - 1) / KT;
@@ -647,7 +753,7 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     g.a_units = (int)a_units;
     g.b_units = v.TAPS > 0 ? KT * OCT : 0;
     if (g.b_units > v.UB * threads) return false;
-    const long long xb = (long long)OCT * g.NB * g.SLOTS * 16 + 16, wb = (long long)taps * OCT * KT * 16;
+    const long long xb = (long long)OCT * g.NB * g.PSLOTS * 16 + 16, wb = (long long)taps * OCT * KT * 16;
     if (16 + 2 * (xb + wb) > LDS_LIMIT) return false;
     g.xbytes = (int)xb;
     g.wbytes = (int)wb;
@@ -671,8 +777,8 @@ double cost(const ConvArgs& a, const Variant& v, const IgemmGeom& g)
     const long long blocks = (long long)g.row_blocks * g.img_blocks * g.k_blocks;
     const long long rounds = (blocks + 255) / 256;
     const int used = (g.NB * g.TH * a.Wo + 31) / 32;
-    int per_wave = (used + v.WM - 1) / v.WM;
-    if (per_wave > v.TM) per_wave = v.TM;
+    // every wave multiplies all TM of its tiles (dead ones included) unless it has none at all
+    const int per_wave = used >= 1 ? v.TM : 0;
     const double mfma = 32.0 * per_wave * v.TN * (a.R * a.S) * (v.CC / 16) * g.n_stages;
     const double overhead = 6000.0 + 1500.0 * g.n_stages;
     const double staged = (double)blocks * g.n_stages * (g.xbytes + g.wbytes) / 256.0 / 64.0;   // 64 B/clk/CU
@@ -682,7 +788,9 @@ double cost(const ConvArgs& a, const Variant& v, const IgemmGeom& g)
 // Developer override: CVX_IGEMM_FORCE="<variant name>,<NB>,<TH>" pins the variant and tile shape.
 bool forced(const ConvArgs& a, const Variant** vout, IgemmGeom* gout)
 {
-    static const char* env = getenv("CVX_IGEMM_FORCE");
+    static const bool present = getenv("CVX_IGEMM_FORCE") != nullptr;   // checked once; re-read only if it was set
+    if (!present) return false;
+    const char* env = getenv("CVX_IGEMM_FORCE");
     if (!env || !*env) return false;
     char name[96];
     int nb = 0, th = 0;
@@ -762,7 +870,7 @@ hipError_t launch_igemm(const ConvArgs& a, hipStream_t s)
         if (e != hipSuccess) return e;
         raised[vi][di] = true;
     }
-    const dim3 grid((unsigned)(g.row_blocks * g.img_blocks * g.k_blocks)), block(v->WM * v->WN * 64);
+    const dim3 grid((unsigned)(g.row_blocks * g.img_blocks * g.k_blocks)), block((v->WM * v->WN + 4) * 64);
     hipLaunchKernelGGL(kern, grid, block, lds, s, a, g);
     return hipGetLastError();
 }
