@@ -1,6 +1,384 @@
-// placeholder until the stem kernel lands
+// Low-channel forward convolution on bf16 / fp16 MFMA for gfx950: the "stem" layer of a CNN
+// (3 input channels, 7x7 filter, stride 2) and shapes like it, where there are too few channels to
+// fill an MFMA's reduction axis and the output store dominates the bytes moved.
+//
+// Fig. 2 of the MIOpen paper stages slices of W and I in LDS, multiplies from registers and writes O
+// once; this kernel keeps that skeleton and the fused bias + activation epilogue of its Sec. V, but
+// lays the reduction out along the filter WIDTH instead of the channels:
+//
+//   reduction index  (c, r, s') with s' = 0..7: one octet = the 8 consecutive input columns that
+//                    filter row r of channel c touches (S <= 8 taps, the rest zero weights).  In NCHW
+//                    those 8 columns are contiguous, so the input goes into LDS as it is -- rows of
+//                    columns per (channel, input row), no transposition -- and an MFMA pixel operand
+//                    is 16 contiguous bytes starting at column q*stride_w - pad_w.
+//   MFMA             v_mfma_f32_32x32x16: lanes 0-31 take octet (c,r) = pair 2j, lanes 32-63 pair 2j+1.
+//   alignment        the LDS row is shifted so that column -pad_w sits at element 0; with an even
+//                    stride_w every operand then starts on a 4-byte boundary (two ds_read2_b32).
+//                    The loader reads device memory 16 bytes at a time from column 8u - pad_w, which
+//                    makes its LDS stores 16-byte aligned (device loads may be 2-byte aligned).
+//   filters in LDS   [pair (c,r)][filter][8 x 16 bit], zero-filled, written once per block.
+//   epilogue         bias / batch-norm / activation in registers, the tile through LDS as
+//                    [filter][pixel], one 16-byte-per-lane store along the pixel axis.
 #include "cvx_device.h"
+
+#include <cstdlib>
+#include <cstring>
+
 namespace cvx {
-bool stem_supported(const ConvArgs&, const char**) { return false; }
-hipError_t launch_stem(const ConvArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+struct StemGeom {
+    int TH;            // output rows per block (tiles span the full output width)
+    int PH;            // input rows a block needs: (TH-1)*stride_h + R
+    int WROW;          // LDS row pitch in elements (multiple of 8, >= W + pad_w + 8)
+    int UPR;           // 16-byte loader units per LDS row
+    int n_units;       // C * PH * UPR
+    int n_pairs;       // C * R  ((channel, filter row) pairs = octets of the reduction)
+    int n_ksteps;      // ceil(n_pairs / 2)
+    int row_blocks, k_blocks;
+    int xbytes, wbytes;
+    uint32_t wo_magic; // ceil(2^32 / Wo) for dividing pixel indices (< 65536) by Wo
+    uint32_t upr_magic;
+};
+
+template <int DT>
+__device__ __forceinline__ f32x16 stem_mfma(u32x4 a, u32x4 b, f32x16 c)
+{
+    if constexpr (DT == DT_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
+
+template <int DT>
+__device__ __forceinline__ uint32_t stem_pack2(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    if constexpr (DT == DT_BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
+__device__ __forceinline__ int div_small(int n, int d, uint32_t magic) { return d == 1 ? n : (int)__umulhi((uint32_t)n, magic); }
+
+// Block: 4 waves, PT = 4*TM*32 pixels (TH full output rows) x KT = TN*32 filters.
+template <int DT, int TM, int TN>
+__global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
+{
+    constexpr int THREADS = 256;
+    constexpr int WAVES = 4;
+    constexpr int PT = WAVES * TM * 32;
+    constexpr int KT = TN * 32;
+    constexpr int PTP = PT + 8;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int HW = a.H * a.W, HoWo = a.Ho * a.Wo;
+    const long long x_total = (long long)a.N * a.C * HW;
+    const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
+    const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
+
+    // block -> (image, row block, filter block); filter blocks of one pixel tile are neighbours
+    int bid = blockIdx.x;
+    const int kb = bid % g.k_blocks;
+    bid /= g.k_blocks;
+    const int rb = bid % g.row_blocks;
+    const int n = bid / g.row_blocks;
+    const int k0 = kb * KT;
+    const int p0 = rb * g.TH;
+    const int rows = min(g.TH, a.Ho - p0);
+    const int npix = rows * a.Wo;
+    const int h_lo = p0 * a.stride_h - a.pad_h;
+
+    unsigned char* xs = smem;                      // input patch  [c][patch row][WROW] x 16 bit
+    unsigned char* ws = smem + g.xbytes;           // filters      [pair][KT][8] x 16 bit
+
+    // ---- input patch: 16-byte units; unit u of an LDS row covers columns 8u - pad_w .. 8u - pad_w + 7
+    for (int ui = tid; ui < g.n_units; ui += THREADS) {
+        const int rowi = div_small(ui, g.UPR, g.upr_magic);       // c * PH + patch row
+        const int u = ui - rowi * g.UPR;
+        const int c = rowi / g.PH;
+        const int pr = rowi - c * g.PH;
+        const int h = h_lo + pr;
+        const int col0 = 8 * u - a.pad_w;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (h >= 0 && h < a.H && col0 < a.W && col0 + 8 > 0) {
+            const long long off = ((long long)(n * a.C + c) * a.H + h) * a.W + col0;
+            if (off >= 0 && off + 8 <= x_total) {
+                v = *(const u32x4_a2*)(xg + off);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const long long o = off + e;
+                    if (o >= 0 && o < x_total) v[e >> 1] |= ((uint32_t)xg[o]) << ((e & 1) * 16);
+                }
+            }
+            // columns outside [0, W) belong to a neighbouring row (or nothing): zero them
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int col = col0 + e;
+                if (col < 0 || col >= a.W) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+            }
+        }
+        *(u32x4*)(xs + ((size_t)rowi * g.WROW + 8 * u) * 2) = v;
+    }
+
+    // ---- filters: one 16-byte unit per (pair = c*R + r, filter): the S <= 8 taps of that filter row
+    //      are contiguous in w[k][c][r][s]; they are fetched with one (2-byte aligned) 16-byte load,
+    //      the elements past S are cleared, and the unit lands at [pair][filter].  Pairs past C*R
+    //      (the odd one out) and filters past K are zero.
+    {
+        const int per_k = a.C * a.R * a.S;
+        const long long w_total = (long long)a.K * per_k;
+        const int n_wunits = 2 * g.n_ksteps * KT;
+        for (int ui = tid; ui < n_wunits; ui += THREADS) {
+            const int kl = ui % KT, pair = ui / KT;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (pair < g.n_pairs && k0 + kl < a.K) {
+                const long long off = (long long)(k0 + kl) * per_k + pair * a.S;
+                if (off + 8 <= w_total) {
+                    v = *(const u32x4_a2*)(wg + off);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (off + e < w_total) v[e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+            }
+            *(u32x4*)(ws + (size_t)ui * 16) = v;
+        }
+    }
+
+    // ---- per-lane operand addresses
+    int xbase[TM];                                   // byte offset of (patch row py*stride_h, column index px*stride_w)
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int f = (tm * WAVES + wave) * 32 + l32;         // pixel tiles dealt round-robin to the waves
+        const int py = div_small(f, a.Wo, g.wo_magic);
+        const int px = f - py * a.Wo;
+        xbase[tm] = f < npix ? ((py * a.stride_h) * g.WROW + px * a.stride_w) * 2 : 0;
+    }
+    const int n_ptiles = (npix + 31) >> 5;
+    const bool wave_on = wave < n_ptiles;
+
+    // epilogue constants of this lane's filters
+    const bool has_bn = a.bn_scale != nullptr;
+    ChannelAffine ca[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(k0 + tn * 32 + l32, a.K - 1));
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const float seed = has_bn ? 0.0f : ca[tn].add;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
+        }
+
+    __syncthreads();
+
+    // ---- reduction: one k-step = two (channel, filter row) pairs, one per half-wave
+    if (wave_on) {
+        int pr = half;                               // this half-wave's pair index
+        int c = 0, r = half;
+        while (r >= a.R) { r -= a.R; ++c; }
+        for (int ks = 0; ks < g.n_ksteps; ++ks) {
+            const bool live = pr < g.n_pairs;        // the odd pair out multiplies zero weights
+            const int rowoff = live ? ((c * g.PH + r) * g.WROW) * 2 : 0;
+            u32x4 fa[TM], fb[TN];
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                fb[tn] = *(const u32x4*)(ws + ((size_t)(live ? pr : 0) * KT + tn * 32 + l32) * 16);
+            if (!live) {
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) fb[tn] = u32x4{0u, 0u, 0u, 0u};
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const uint32_t* p = (const uint32_t*)(xs + xbase[tm] + rowoff);   // 4-byte aligned
+                fa[tm] = u32x4{p[0], p[1], p[2], p[3]};
+            }
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = stem_mfma<DT>(fa[tm], fb[tn], acc[tm][tn]);
+            pr += 2;
+            r += 2;
+            while (r >= a.R) { r -= a.R; ++c; }
+        }
+    }
+    __syncthreads();                                 // all operand reads done: LDS becomes the output tile
+
+    // ---- epilogue part 1: registers -> LDS as [filter][pixel] in the output type
+    uint16_t* ot = (uint16_t*)smem;
+    if (wave_on) {
+        auto stage_out = [&](auto&& act_fn) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const int kl = tn * 32 + l32;
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                    for (int q4 = 0; q4 < 4; ++q4) {
+                        float v[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float t = acc[tm][tn][4 * q4 + j];
+                            v[j] = act_fn(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t);
+                        }
+                        const int f = (tm * WAVES + wave) * 32 + 8 * q4 + 4 * half;
+                        *(uint2*)(ot + kl * PTP + f) = make_uint2(stem_pack2<DT>(v[0], v[1]), stem_pack2<DT>(v[2], v[3]));
+                    }
+                }
+            }
+        };
+        if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
+        else if (a.act == ACT_IDENTITY) stage_out([](float t) { return t; });
+        else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
+    }
+    __syncthreads();
+
+    // ---- epilogue part 2: the single store, 16 bytes per lane along the pixel axis
+    {
+        constexpr int CH = PT / 8;
+        constexpr int RSTEP = THREADS / CH;
+        constexpr int NPASS = (KT + RSTEP - 1) / RSTEP;
+        const int chunk = tid % CH, row0 = tid / CH;
+        const int f0 = chunk * 8;
+        if (f0 < npix) {
+            const bool whole = f0 + 8 <= npix;
+            uint16_t* __restrict__ yg = (uint16_t*)a.y;
+            const size_t obase = ((size_t)n * a.K + k0) * HoWo + (size_t)p0 * a.Wo + f0;
+            constexpr int GRP = NPASS >= 4 ? 4 : NPASS;
+            for (int p = 0; p < NPASS; p += GRP) {
+                u32x4 v[GRP];
+#pragma unroll
+                for (int j = 0; j < GRP; ++j) v[j] = *(const u32x4*)(ot + min(row0 + (p + j) * RSTEP, KT - 1) * PTP + f0);
+#pragma unroll
+                for (int j = 0; j < GRP; ++j) {
+                    const int kl = row0 + (p + j) * RSTEP;
+                    if (kl < KT && k0 + kl < a.K) {
+                        uint16_t* dst = yg + obase + (size_t)kl * HoWo;
+                        if (whole) {
+                            *(u32x4_a2*)dst = v[j];
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (f0 + e < npix) dst[e] = (uint16_t)(v[j][e >> 1] >> ((e & 1) * 16));
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int STEM_LDS_LIMIT = 64 * 1024;     // stays under the default dynamic-LDS limit
+
+struct StemVariant {
+    const char* name;
+    int TM, TN;
+    void (*kern_bf16)(ConvArgs, StemGeom);
+    void (*kern_f16)(ConvArgs, StemGeom);
+};
+
+const StemVariant kStem[] = {
+    {"stem_256x64", 2, 2, stem_kernel<DT_BF16, 2, 2>, stem_kernel<DT_F16, 2, 2>},
+    {"stem_128x64", 1, 2, stem_kernel<DT_BF16, 1, 2>, stem_kernel<DT_F16, 1, 2>},
+};
+
+bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
+{
+    if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
+    if (a.groups != 1) return false;
+    if (a.C > 4 || a.S > 8 || a.R > 16) return false;              // low-channel layers only
+    if (a.dil_h != 1 || a.dil_w != 1) return false;
+    if ((a.stride_w & 1) || a.stride_w > 8) return false;          // operands must start 4-byte aligned
+    if (a.Wo >= 32768 || a.W >= 32768) return false;
+    const long long xbytes = (long long)a.N * a.C * a.H * a.W * 2, ybytes = (long long)a.N * a.K * a.Ho * a.Wo * 2;
+    if (xbytes >= (1LL << 31) || ybytes >= (1LL << 31)) return false;
+    if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y) & 15) return false;
+    if (const char* e = getenv("CVX_STEM_OFF")) {
+        if (*e && *e != '0') return false;
+    }
+    for (const StemVariant& v : kStem) {
+        const int PT = 4 * v.TM * 32, KT = v.TN * 32;
+        if (a.Wo > PT) continue;
+        StemGeom g;
+        g.TH = PT / a.Wo;
+        if (g.TH > a.Ho) g.TH = a.Ho;
+        g.PH = (g.TH - 1) * a.stride_h + a.R;
+        // the last pixel's operand reads 8 columns from (Wo-1)*stride_w; rows are zero-filled up to WROW
+        const int need = (a.Wo - 1) * a.stride_w + 8;
+        const int have = a.W + a.pad_w;
+        g.WROW = ((need > have ? need : have) + 7) & ~7;
+        g.UPR = g.WROW / 8;
+        g.n_units = a.C * g.PH * g.UPR;
+        g.n_pairs = a.C * a.R;
+        g.n_ksteps = (g.n_pairs + 1) / 2;
+        g.row_blocks = (a.Ho + g.TH - 1) / g.TH;
+        g.k_blocks = (a.K + KT - 1) / KT;
+        g.xbytes = a.C * g.PH * g.WROW * 2;
+        g.wbytes = 2 * g.n_ksteps * KT * 16;
+        const int otile = KT * (PT + 8) * 2;
+        const int lds = g.xbytes + g.wbytes > otile ? g.xbytes + g.wbytes : otile;
+        if (lds > STEM_LDS_LIMIT) continue;
+        if (g.n_units >= 65536) continue;
+        if ((long long)a.N * g.row_blocks * g.k_blocks > 0x7fffffffLL) continue;
+        g.wo_magic = a.Wo > 1 ? (uint32_t)(((1ull << 32) + a.Wo - 1) / a.Wo) : 0u;
+        g.upr_magic = g.UPR > 1 ? (uint32_t)(((1ull << 32) + g.UPR - 1) / g.UPR) : 0u;
+        // prefer the variant that wastes fewer pixel slots
+        const int used = g.TH * a.Wo;
+        if (used * 4 < PT * 3 && &v != &kStem[sizeof(kStem) / sizeof(kStem[0]) - 1]) {
+            // try the smaller tile first if this one would be mostly empty
+            continue;
+        }
+        *vout = &v;
+        *gout = g;
+        return true;
+    }
+    return false;
+}
+
+}  // namespace
+
+bool stem_supported(const ConvArgs& a, const char** variant_name)
+{
+    const StemVariant* v;
+    StemGeom g;
+    if (!stem_plan(a, &v, &g)) return false;
+    if (variant_name) *variant_name = v->name;
+    return true;
+}
+
+hipError_t launch_stem(const ConvArgs& a, hipStream_t s)
+{
+    const StemVariant* v;
+    StemGeom g;
+    if (!stem_plan(a, &v, &g)) return hipErrorInvalidValue;
+    auto kern = a.dtype == DT_BF16 ? v->kern_bf16 : v->kern_f16;
+    const int PT = 4 * v->TM * 32, KT = v->TN * 32;
+    const int otile = KT * (PT + 8) * 2;
+    const int lds = g.xbytes + g.wbytes > otile ? g.xbytes + g.wbytes : otile;
+    const dim3 grid((unsigned)(a.N * g.row_blocks * g.k_blocks)), block(256);
+    hipLaunchKernelGGL(kern, grid, block, lds, s, a, g);
+    return hipGetLastError();
+}
+
+}  // namespace cvx

@@ -62,6 +62,10 @@ SMALL = [
     _v("c4", name="c4_n2", N=2),
     _v("c4", name="c4_ragged", N=2, H=61, W=45, K=24),
     _v("c4", name="c4_bf16", N=1, H=64, W=64, dtype=wl.BF16),
+    _v("c4", name="stem_k96_c4", N=2, C=4, H=50, W=66, K=96),
+    _v("c4", name="stem_c1_5x3_pad0", N=2, C=1, H=33, W=40, K=16, R=5, S=3, pad=(0, 0), stride=(1, 2)),
+    _v("c4", name="stem_3x8_stride4", N=1, C=2, H=20, W=70, K=8, R=3, S=8, pad=(1, 5), stride=(3, 4)),
+    _v("c4", name="stem_narrow", N=3, C=3, H=9, W=9, K=5),
     _v("c5a", name="c5a_small", N=6, C=64, K=96),
     _v("c5b", name="c5b_small", N=3, C=64, K=48),
     _v("c5b", name="c5b_odd", N=2, C=32, K=32, H=27, W=25),
