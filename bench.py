@@ -142,6 +142,9 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--all", action="store_true", help="also time every layer; table to stderr and gpurun_out/bench_all.json")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (no parity check, no cpu_baseline)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="first run one plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (forward convolution shards over the batch with no "
@@ -152,6 +155,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     r = time_workload(args.workload, args.steps, args.warmup, check=not args.no_cpu)
     w = r["workload"]

@@ -96,4 +96,23 @@ __device__ __forceinline__ float finish(float acc, const ChannelAffine& ca, bool
     return activate(v, act, alpha);
 }
 
+// Developer facility, compiled out unless CVX_PHASE_TRACE is defined: thread 0 of every block
+// records wall-clock timestamps (100 MHz) at phase boundaries into a caller-provided buffer of
+// 32 slots per block (16 wall-clock stamps, then 16 shader-clock stamps).
+#ifdef CVX_PHASE_TRACE
+static __device__ unsigned long long* g_phase_trace = nullptr;   // one per translation unit
+#define CVX_TRACE_MARK(slot) CVX_TRACE_MARK_T(slot, 0)
+#define CVX_TRACE_MARK_T(slot, t)                                                                 \
+    do {                                                                                          \
+        if (threadIdx.x == (t) && g_phase_trace) {                                                  \
+            g_phase_trace[(size_t)blockIdx.x * 32 + (slot)] = wall_clock64();                     \
+            g_phase_trace[(size_t)blockIdx.x * 32 + 16 + (slot)] = clock64();                     \
+        }                                                                                         \
+    } while (0)
+#else
+#define CVX_TRACE_MARK(slot) do { } while (0)
+#define CVX_TRACE_MARK_T(slot, t) do { } while (0)
+#endif
+
+
 }  // namespace cvx

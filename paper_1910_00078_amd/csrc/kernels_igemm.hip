@@ -33,24 +33,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
-// Developer facility, compiled out unless CVX_PHASE_TRACE is defined: thread 0 of every block
-// records wall-clock timestamps (100 MHz) at phase boundaries into a caller-provided buffer of
-// 32 slots per block (16 wall-clock stamps, then 16 shader-clock stamps).
-#ifdef CVX_PHASE_TRACE
-__device__ unsigned long long* g_phase_trace = nullptr;
-#define CVX_TRACE_MARK(slot) CVX_TRACE_MARK_T(slot, 0)
-#define CVX_TRACE_MARK_T(slot, t)                                                                 \
-    do {                                                                                          \
-        if (threadIdx.x == (t) && g_phase_trace) {                                                  \
-            g_phase_trace[(size_t)blockIdx.x * 32 + (slot)] = wall_clock64();                     \
-            g_phase_trace[(size_t)blockIdx.x * 32 + 16 + (slot)] = clock64();                     \
-        }                                                                                         \
-    } while (0)
-#else
-#define CVX_TRACE_MARK(slot) do { } while (0)
-#define CVX_TRACE_MARK_T(slot, t) do { } while (0)
-#endif
-
 // Division of small non-negative integers by a runtime divisor chosen on the host: q = n / d for
 // n, d < 65536 via one multiply-high (m = ceil(2^32 / d); exact while n * d < 2^32).
 struct FastDiv {

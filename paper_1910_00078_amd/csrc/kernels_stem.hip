@@ -47,6 +47,7 @@ struct StemGeom {
     int xbytes, wbytes;
     uint32_t wo_magic; // ceil(2^32 / Wo) for dividing pixel indices (< 65536) by Wo
     uint32_t upr_magic;
+    uint32_t ph_magic;
 };
 
 template <int DT>
@@ -68,7 +69,12 @@ __device__ __forceinline__ uint32_t stem_pack2(float lo, float hi)
 
 __device__ __forceinline__ int div_small(int n, int d, uint32_t magic) { return d == 1 ? n : (int)__umulhi((uint32_t)n, magic); }
 
-// Block: 4 waves, PT = 4*TM*32 pixels (TH full output rows) x KT = TN*32 filters.
+// Block: 4 waves, PT = 4*TM*32 pixels (TH full output rows) x KT = TN*32 filters.  Blocks are
+// persistent: block b works through tiles b, b + gridDim.x, ... with the filters resident in LDS and
+// the loop software-pipelined -- the input patch of the next tile is fetched into registers while the
+// current one is multiplied, and the stores of the current tile drain while the next one starts.
+//
+// LDS map: filters [pair][KT][8] | input patch [c][patch row][WROW] | output tile [KT][PT + 8].
 template <int DT, int TM, int TN>
 __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
 {
@@ -77,219 +83,292 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
     constexpr int PT = WAVES * TM * 32;
     constexpr int KT = TN * 32;
     constexpr int PTP = PT + 8;
+    constexpr int XU = 4;                            // input loader units per thread (host guarantees enough)
+    constexpr int WU = 6;                            // filter loader units per thread and batch
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
+    CVX_TRACE_MARK(0);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int HW = a.H * a.W, HoWo = a.Ho * a.Wo;
-    const long long x_total = (long long)a.N * a.C * HW;
+    const int HoWo = a.Ho * a.Wo;
+    const long long x_total = (long long)a.N * a.C * a.H * a.W;
     const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
     const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
+    uint16_t* __restrict__ yg = (uint16_t*)a.y;
 
-    // block -> (image, row block, filter block); filter blocks of one pixel tile are neighbours
-    int bid = blockIdx.x;
-    const int kb = bid % g.k_blocks;
-    bid /= g.k_blocks;
-    const int rb = bid % g.row_blocks;
-    const int n = bid / g.row_blocks;
-    const int k0 = kb * KT;
-    const int p0 = rb * g.TH;
-    const int rows = min(g.TH, a.Ho - p0);
-    const int npix = rows * a.Wo;
-    const int h_lo = p0 * a.stride_h - a.pad_h;
+    unsigned char* ws = smem;                            // filters
+    unsigned char* xs = smem + g.wbytes;                 // input patch
+    uint16_t* ot = (uint16_t*)(smem + g.wbytes + g.xbytes);   // output tile
 
-    unsigned char* xs = smem;                      // input patch  [c][patch row][WROW] x 16 bit
-    unsigned char* ws = smem + g.xbytes;           // filters      [pair][KT][8] x 16 bit
+    const int tiles_per_kb = a.N * g.row_blocks;
+    const int n_tiles = tiles_per_kb * g.k_blocks;
 
-    // ---- input patch: 16-byte units; unit u of an LDS row covers columns 8u - pad_w .. 8u - pad_w + 7
-    for (int ui = tid; ui < g.n_units; ui += THREADS) {
-        const int rowi = div_small(ui, g.UPR, g.upr_magic);       // c * PH + patch row
-        const int u = ui - rowi * g.UPR;
-        const int c = rowi / g.PH;
-        const int pr = rowi - c * g.PH;
-        const int h = h_lo + pr;
-        const int col0 = 8 * u - a.pad_w;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (h >= 0 && h < a.H && col0 < a.W && col0 + 8 > 0) {
-            const long long off = ((long long)(n * a.C + c) * a.H + h) * a.W + col0;
-            if (off >= 0 && off + 8 <= x_total) {
-                v = *(const u32x4_a2*)(xg + off);
-            } else {
+    // ---- tile-independent bookkeeping
+    // input loader units: unit u of LDS row rowi = c*PH + patch row covers columns 8u - pad_w .. +7
+    int x_dst[XU], x_c[XU], x_pr[XU], x_col[XU];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const long long o = off + e;
-                    if (o >= 0 && o < x_total) v[e >> 1] |= ((uint32_t)xg[o]) << ((e & 1) * 16);
-                }
-            }
-            // columns outside [0, W) belong to a neighbouring row (or nothing): zero them
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int col = col0 + e;
-                if (col < 0 || col >= a.W) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-            }
-        }
-        *(u32x4*)(xs + ((size_t)rowi * g.WROW + 8 * u) * 2) = v;
-    }
-
-    // ---- filters: one 16-byte unit per (pair = c*R + r, filter): the S <= 8 taps of that filter row
-    //      are contiguous in w[k][c][r][s]; they are fetched with one (2-byte aligned) 16-byte load,
-    //      the elements past S are cleared, and the unit lands at [pair][filter].  Pairs past C*R
-    //      (the odd one out) and filters past K are zero.
-    {
-        const int per_k = a.C * a.R * a.S;
-        const long long w_total = (long long)a.K * per_k;
-        const int n_wunits = 2 * g.n_ksteps * KT;
-        for (int ui = tid; ui < n_wunits; ui += THREADS) {
-            const int kl = ui % KT, pair = ui / KT;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (pair < g.n_pairs && k0 + kl < a.K) {
-                const long long off = (long long)(k0 + kl) * per_k + pair * a.S;
-                if (off + 8 <= w_total) {
-                    v = *(const u32x4_a2*)(wg + off);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (off + e < w_total) v[e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-            }
-            *(u32x4*)(ws + (size_t)ui * 16) = v;
+    for (int j = 0; j < XU; ++j) {
+        const int ui = j * THREADS + tid;
+        x_dst[j] = -1;
+        x_c[j] = x_pr[j] = x_col[j] = 0;
+        if (ui < g.n_units) {
+            const int rowi = div_small(ui, g.UPR, g.upr_magic);
+            const int u = ui - rowi * g.UPR;
+            x_c[j] = div_small(rowi, g.PH, g.ph_magic);
+            x_pr[j] = rowi - x_c[j] * g.PH;
+            x_col[j] = 8 * u - a.pad_w;
+            x_dst[j] = (rowi * g.WROW + 8 * u) * 2;
         }
     }
-
-    // ---- per-lane operand addresses
-    int xbase[TM];                                   // byte offset of (patch row py*stride_h, column index px*stride_w)
+    // operand addresses: byte offset of (patch row py*stride_h, column index px*stride_w) per pixel tile
+    int xbase[TM];
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int f = (tm * WAVES + wave) * 32 + l32;         // pixel tiles dealt round-robin to the waves
         const int py = div_small(f, a.Wo, g.wo_magic);
         const int px = f - py * a.Wo;
-        xbase[tm] = f < npix ? ((py * a.stride_h) * g.WROW + px * a.stride_w) * 2 : 0;
+        xbase[tm] = f < g.TH * a.Wo ? ((py * a.stride_h) * g.WROW + px * a.stride_w) * 2 : 0;
     }
-    const int n_ptiles = (npix + 31) >> 5;
-    const bool wave_on = wave < n_ptiles;
-
-    // epilogue constants of this lane's filters
     const bool has_bn = a.bn_scale != nullptr;
-    ChannelAffine ca[TN];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(k0 + tn * 32 + l32, a.K - 1));
 
-    f32x16 acc[TM][TN];
+    // Issues the loads of one tile's input patch (nothing here uses a loaded value).
+    auto load_patch = [&](int tile, u32x4 (&xv)[XU]) __attribute__((always_inline)) {
+        const int pt = tile % tiles_per_kb;
+        const int n = pt / g.row_blocks;
+        const int rb = pt - n * g.row_blocks;
+        const int h_lo = rb * g.TH * a.stride_h - a.pad_h;
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+        for (int j = 0; j < XU; ++j) {
+            xv[j] = u32x4{0u, 0u, 0u, 0u};
+            const int h = h_lo + x_pr[j];
+            if (x_dst[j] >= 0 && h >= 0 && h < a.H && x_col[j] < a.W && x_col[j] + 8 > 0) {
+                const long long off = ((long long)(n * a.C + x_c[j]) * a.H + h) * a.W + x_col[j];
+                if (off >= 0 && off + 8 <= x_total) {
+                    xv[j] = *(const u32x4_a2*)(xg + off);
+                } else {
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn) {
-            const float seed = has_bn ? 0.0f : ca[tn].add;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
-        }
-
-    __syncthreads();
-
-    // ---- reduction: one k-step = two (channel, filter row) pairs, one per half-wave
-    if (wave_on) {
-        int pr = half;                               // this half-wave's pair index
-        int c = 0, r = half;
-        while (r >= a.R) { r -= a.R; ++c; }
-        for (int ks = 0; ks < g.n_ksteps; ++ks) {
-            const bool live = pr < g.n_pairs;        // the odd pair out multiplies zero weights
-            const int rowoff = live ? ((c * g.PH + r) * g.WROW) * 2 : 0;
-            u32x4 fa[TM], fb[TN];
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                fb[tn] = *(const u32x4*)(ws + ((size_t)(live ? pr : 0) * KT + tn * 32 + l32) * 16);
-            if (!live) {
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) fb[tn] = u32x4{0u, 0u, 0u, 0u};
-            }
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const uint32_t* p = (const uint32_t*)(xs + xbase[tm] + rowoff);   // 4-byte aligned
-                fa[tm] = u32x4{p[0], p[1], p[2], p[3]};
-            }
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = stem_mfma<DT>(fa[tm], fb[tn], acc[tm][tn]);
-            pr += 2;
-            r += 2;
-            while (r >= a.R) { r -= a.R; ++c; }
-        }
-    }
-    __syncthreads();                                 // all operand reads done: LDS becomes the output tile
-
-    // ---- epilogue part 1: registers -> LDS as [filter][pixel] in the output type
-    uint16_t* ot = (uint16_t*)smem;
-    if (wave_on) {
-        auto stage_out = [&](auto&& act_fn) {
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                const int kl = tn * 32 + l32;
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        float v[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float t = acc[tm][tn][4 * q4 + j];
-                            v[j] = act_fn(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t);
-                        }
-                        const int f = (tm * WAVES + wave) * 32 + 8 * q4 + 4 * half;
-                        *(uint2*)(ot + kl * PTP + f) = make_uint2(stem_pack2<DT>(v[0], v[1]), stem_pack2<DT>(v[2], v[3]));
+                    for (int e = 0; e < 8; ++e) {
+                        const long long o = off + e;
+                        if (o >= 0 && o < x_total) xv[j][e >> 1] |= ((uint32_t)xg[o]) << ((e & 1) * 16);
                     }
                 }
             }
-        };
-        if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
-        else if (a.act == ACT_IDENTITY) stage_out([](float t) { return t; });
-        else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
-    }
-    __syncthreads();
-
-    // ---- epilogue part 2: the single store, 16 bytes per lane along the pixel axis
-    {
-        constexpr int CH = PT / 8;
-        constexpr int RSTEP = THREADS / CH;
-        constexpr int NPASS = (KT + RSTEP - 1) / RSTEP;
-        const int chunk = tid % CH, row0 = tid / CH;
-        const int f0 = chunk * 8;
-        if (f0 < npix) {
-            const bool whole = f0 + 8 <= npix;
-            uint16_t* __restrict__ yg = (uint16_t*)a.y;
-            const size_t obase = ((size_t)n * a.K + k0) * HoWo + (size_t)p0 * a.Wo + f0;
-            constexpr int GRP = NPASS >= 4 ? 4 : NPASS;
-            for (int p = 0; p < NPASS; p += GRP) {
-                u32x4 v[GRP];
+        }
+    };
+    // Clears the columns outside [0, W) (they belong to a neighbouring row, or to nothing) and writes
+    // the patch into LDS.
+    auto store_patch = [&](const u32x4 (&xv)[XU]) __attribute__((always_inline)) {
 #pragma unroll
-                for (int j = 0; j < GRP; ++j) v[j] = *(const u32x4*)(ot + min(row0 + (p + j) * RSTEP, KT - 1) * PTP + f0);
+        for (int j = 0; j < XU; ++j) {
+            if (x_dst[j] >= 0) {
+                u32x4 v = xv[j];
 #pragma unroll
-                for (int j = 0; j < GRP; ++j) {
-                    const int kl = row0 + (p + j) * RSTEP;
-                    if (kl < KT && k0 + kl < a.K) {
-                        uint16_t* dst = yg + obase + (size_t)kl * HoWo;
-                        if (whole) {
-                            *(u32x4_a2*)dst = v[j];
+                for (int e = 0; e < 8; ++e) {
+                    const int col = x_col[j] + e;
+                    if (col < 0 || col >= a.W) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                }
+                *(u32x4*)(xs + x_dst[j]) = v;
+            }
+        }
+    };
+    // Filters of filter block kb: one 16-byte unit per (pair = c*R + r, filter): the S <= 8 taps of a
+    // filter row are contiguous in w[k][c][r][s]; one (2-byte aligned) 16-byte load fetches them, the
+    // elements past S are cleared, and the unit lands at [pair][filter].  Pairs past C*R (the odd one
+    // out) and filters past K are zero.  All loads of a batch are issued before any is used.
+    auto load_filters = [&](int k0) __attribute__((always_inline)) {
+        const int per_k = a.C * a.R * a.S;
+        const long long w_total = (long long)a.K * per_k;
+        const int n_wunits = 2 * g.n_ksteps * KT;
+        for (int base = 0; base < n_wunits; base += THREADS * WU) {
+            u32x4 wv[WU];
+#pragma unroll
+            for (int j = 0; j < WU; ++j) {
+                const int ui = base + j * THREADS + tid;
+                wv[j] = u32x4{0u, 0u, 0u, 0u};
+                if (ui < n_wunits) {
+                    const int kl = ui % KT, pair = ui / KT;
+                    if (pair < g.n_pairs && k0 + kl < a.K) {
+                        const long long off = (long long)(k0 + kl) * per_k + pair * a.S;
+                        if (off + 8 <= w_total) {
+                            wv[j] = *(const u32x4_a2*)(wg + off);
                         } else {
 #pragma unroll
                             for (int e = 0; e < 8; ++e)
-                                if (f0 + e < npix) dst[e] = (uint16_t)(v[j][e >> 1] >> ((e & 1) * 16));
+                                if (off + e < w_total) wv[j][e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < WU; ++j) {
+                const int ui = base + j * THREADS + tid;
+                if (ui < n_wunits) {
+                    u32x4 v = wv[j];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                    *(u32x4*)(ws + (size_t)ui * 16) = v;
+                }
+            }
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile >= n_tiles) return;
+    int cur_kb = -1;
+    u32x4 xv[XU];
+    load_patch(tile, xv);
+
+    for (; tile < n_tiles; tile += gridDim.x) {
+        const int kb = tile / tiles_per_kb;
+        const int pt = tile - kb * tiles_per_kb;
+        const int n = pt / g.row_blocks;
+        const int rb = pt - n * g.row_blocks;
+        const int k0 = kb * KT;
+        const int p0 = rb * g.TH;
+        const int npix = min(g.TH, a.Ho - p0) * a.Wo;
+        const bool wave_on = wave < ((npix + 31) >> 5);
+
+        // (1) this tile's patch (in registers since the previous pass) -> LDS; filters if they changed.
+        //     The previous pass has finished reading xs and ws before its last barrier.
+        store_patch(xv);
+        if (kb != cur_kb) {
+            load_filters(k0);
+            cur_kb = kb;
+        }
+        __syncthreads();
+        CVX_TRACE_MARK(2);
+
+        // (2) start fetching the next tile's patch
+        if (tile + gridDim.x < n_tiles) load_patch(tile + gridDim.x, xv);
+
+        // (3) multiply.  One k-step = two (channel, filter row) pairs, one per half-wave; the fragments of
+        //     step ks+1 are read before the MFMAs of step ks are issued (two register sets).
+        ChannelAffine ca[TN];
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(k0 + tn * 32 + l32, a.K - 1));
+        f32x16 acc[TM][TN];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                const float seed = has_bn ? 0.0f : ca[tn].add;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
+            }
+        if (wave_on) {
+            int pr = half;                               // this half-wave's pair index
+            int c = 0, r = half;
+            while (r >= a.R) { r -= a.R; ++c; }
+            auto read_step = [&](u32x4 (&fa)[TM], u32x4 (&fb)[TN]) __attribute__((always_inline)) {
+                const bool live = pr < g.n_pairs;        // the odd pair out multiplies zero weights
+                const int rowoff = live ? ((c * g.PH + r) * g.WROW) * 2 : 0;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    fb[tn] = *(const u32x4*)(ws + ((size_t)pr * KT + tn * 32 + l32) * 16);   // dead pairs hold zeros
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+                    const uint32_t* p = (const uint32_t*)(xs + xbase[tm] + rowoff);   // 4-byte aligned
+                    fa[tm] = u32x4{p[0], p[1], p[2], p[3]};
+                }
+                pr += 2;
+                r += 2;
+                while (r >= a.R) { r -= a.R; ++c; }
+            };
+            auto mul_step = [&](const u32x4 (&fa)[TM], const u32x4 (&fb)[TN]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = stem_mfma<DT>(fa[tm], fb[tn], acc[tm][tn]);
+            };
+            u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+            read_step(fa0, fb0);
+            for (int ks = 0; ks < g.n_ksteps; ks += 2) {
+                if (ks + 1 < g.n_ksteps) read_step(fa1, fb1);
+                __builtin_amdgcn_sched_barrier(0);
+                mul_step(fa0, fb0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (ks + 1 < g.n_ksteps) {
+                    if (ks + 2 < g.n_ksteps) read_step(fa0, fb0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    mul_step(fa1, fb1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        CVX_TRACE_MARK(5);
+
+        // (4) epilogue part 1: registers -> LDS as [filter][pixel] in the output type.  The output tile
+        //     has its own LDS region; the previous pass's store loop finished reading it before (1).
+        if (wave_on) {
+            auto stage_out = [&](auto&& act_fn) __attribute__((always_inline)) {
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int kl = tn * 32 + l32;
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            float v[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const float t = acc[tm][tn][4 * q4 + j];
+                                v[j] = act_fn(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t);
+                            }
+                            const int f = (tm * WAVES + wave) * 32 + 8 * q4 + 4 * half;
+                            *(uint2*)(ot + kl * PTP + f) = make_uint2(stem_pack2<DT>(v[0], v[1]), stem_pack2<DT>(v[2], v[3]));
+                        }
+                    }
+                }
+            };
+            if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
+            else if (a.act == ACT_IDENTITY) stage_out([](float t) { return t; });
+            else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
+        }
+        __syncthreads();                             // output tile complete; all reads of xs / ws done
+        CVX_TRACE_MARK(6);
+
+        // (5) epilogue part 2: the single store, 16 bytes per lane along the pixel axis
+        {
+            constexpr int CH = PT / 8;
+            constexpr int RSTEP = THREADS / CH;
+            constexpr int NPASS = (KT + RSTEP - 1) / RSTEP;
+            const int chunk = tid % CH, row0 = tid / CH;
+            const int f0 = chunk * 8;
+            if (f0 < npix) {
+                const bool whole = f0 + 8 <= npix;
+                const size_t obase = ((size_t)n * a.K + k0) * HoWo + (size_t)p0 * a.Wo + f0;
+                constexpr int GRP = NPASS >= 4 ? 4 : NPASS;
+                for (int p = 0; p < NPASS; p += GRP) {
+                    u32x4 v[GRP];
+#pragma unroll
+                    for (int j = 0; j < GRP; ++j) v[j] = *(const u32x4*)(ot + min(row0 + (p + j) * RSTEP, KT - 1) * PTP + f0);
+#pragma unroll
+                    for (int j = 0; j < GRP; ++j) {
+                        const int kl = row0 + (p + j) * RSTEP;
+                        if (kl < KT && k0 + kl < a.K) {
+                            uint16_t* dst = yg + obase + (size_t)kl * HoWo;
+                            if (whole) {
+                                *(u32x4_a2*)dst = v[j];
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    if (f0 + e < npix) dst[e] = (uint16_t)(v[j][e >> 1] >> ((e & 1) * 16));
+                            }
                         }
                     }
                 }
             }
         }
+        CVX_TRACE_MARK(15);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 namespace {
 
-constexpr int STEM_LDS_LIMIT = 64 * 1024;     // stays under the default dynamic-LDS limit
+constexpr int STEM_LDS_LIMIT = 80 * 1024;     // two blocks per CU
 
 struct StemVariant {
     const char* name;
@@ -337,12 +416,13 @@ bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
         g.xbytes = a.C * g.PH * g.WROW * 2;
         g.wbytes = 2 * g.n_ksteps * KT * 16;
         const int otile = KT * (PT + 8) * 2;
-        const int lds = g.xbytes + g.wbytes > otile ? g.xbytes + g.wbytes : otile;
+        const int lds = g.xbytes + g.wbytes + otile;
         if (lds > STEM_LDS_LIMIT) continue;
-        if (g.n_units >= 65536) continue;
+        if (g.n_units > 4 * 256) continue;                         // 4 loader units per thread
         if ((long long)a.N * g.row_blocks * g.k_blocks > 0x7fffffffLL) continue;
         g.wo_magic = a.Wo > 1 ? (uint32_t)(((1ull << 32) + a.Wo - 1) / a.Wo) : 0u;
         g.upr_magic = g.UPR > 1 ? (uint32_t)(((1ull << 32) + g.UPR - 1) / g.UPR) : 0u;
+        g.ph_magic = g.PH > 1 ? (uint32_t)(((1ull << 32) + g.PH - 1) / g.PH) : 0u;
         // prefer the variant that wastes fewer pixel slots
         const int used = g.TH * a.Wo;
         if (used * 4 < PT * 3 && &v != &kStem[sizeof(kStem) / sizeof(kStem[0]) - 1]) {
@@ -357,6 +437,13 @@ bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
 }
 
 }  // namespace
+
+#ifdef CVX_PHASE_TRACE
+extern "C" int cvx_debug_set_phase_trace_stem(unsigned long long* device_buffer)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_phase_trace), &device_buffer, sizeof(device_buffer));
+}
+#endif
 
 bool stem_supported(const ConvArgs& a, const char** variant_name)
 {
@@ -375,8 +462,22 @@ hipError_t launch_stem(const ConvArgs& a, hipStream_t s)
     auto kern = a.dtype == DT_BF16 ? v->kern_bf16 : v->kern_f16;
     const int PT = 4 * v->TM * 32, KT = v->TN * 32;
     const int otile = KT * (PT + 8) * 2;
-    const int lds = g.xbytes + g.wbytes > otile ? g.xbytes + g.wbytes : otile;
-    const dim3 grid((unsigned)(a.N * g.row_blocks * g.k_blocks)), block(256);
+    const int lds = g.xbytes + g.wbytes + otile;
+    static bool raised[2][2];
+    const int vi = (int)(v - kStem), di = a.dtype == DT_BF16 ? 0 : 1;
+    if (!raised[vi][di]) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, STEM_LDS_LIMIT);
+        if (e != hipSuccess) return e;
+        raised[vi][di] = true;
+    }
+    // persistent blocks: as many as stay resident at once (LDS decides), each striding through the tiles
+    const long long tiles = (long long)a.N * g.row_blocks * g.k_blocks;
+    int per_cu = (160 * 1024) / lds;
+    if (per_cu > 4) per_cu = 4;
+    if (per_cu < 1) per_cu = 1;
+    long long blocks = 256LL * per_cu;
+    if (blocks > tiles) blocks = tiles;
+    const dim3 grid((unsigned)blocks), block(256);
     hipLaunchKernelGGL(kern, grid, block, lds, s, a, g);
     return hipGetLastError();
 }
