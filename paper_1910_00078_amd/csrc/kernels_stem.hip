@@ -75,7 +75,7 @@ __device__ __forceinline__ int div_small(int n, int d, uint32_t magic) { return 
 // current one is multiplied, and the stores of the current tile drain while the next one starts.
 //
 // LDS map: filters [pair][KT][8] | input patch [c][patch row][WROW] | output tile [KT][PT + 8].
-template <int DT, int TM, int TN>
+template <int DT, int TM, int TN, int NKS>
 __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
 {
     constexpr int THREADS = 256;
@@ -131,6 +131,19 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
         xbase[tm] = f < g.TH * a.Wo ? ((py * a.stride_h) * g.WROW + px * a.stride_w) * 2 : 0;
     }
     const bool has_bn = a.bn_scale != nullptr;
+    // With a compile-time number of k-steps (NKS > 0) the byte offset of every step's (channel, filter
+    // row) pair is worked out once; the reduction loop is then straight-line code.
+    int rowoff[NKS > 0 ? NKS : 1];
+    if constexpr (NKS > 0) {
+        int c = 0, r = half;
+        while (r >= a.R) { r -= a.R; ++c; }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            rowoff[ks] = (2 * ks + half) < g.n_pairs ? ((c * g.PH + r) * g.WROW) * 2 : 0;
+            r += 2;
+            while (r >= a.R) { r -= a.R; ++c; }
+        }
+    }
 
     // Issues the loads of one tile's input patch (nothing here uses a loaded value).
     auto load_patch = [&](int tile, u32x4 (&xv)[XU]) __attribute__((always_inline)) {
@@ -217,8 +230,28 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
     int tile = blockIdx.x;
     if (tile >= n_tiles) return;
     int cur_kb = -1;
+    ChannelAffine ca[TN];                            // epilogue constants of this lane's filters
     u32x4 xv[XU];
+
+    // Brings a tile's patch (already in xv) into LDS, and the filters and epilogue constants if the
+    // filter block changed (once per block unless K > KT).
+    auto enter_tile = [&](int tl) __attribute__((always_inline)) {
+        store_patch(xv);
+        const int kb = tl / tiles_per_kb;
+        if (kb != cur_kb) {
+            load_filters(kb * KT);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(kb * KT + tn * 32 + l32, a.K - 1));
+            cur_kb = kb;
+        }
+    };
+
     load_patch(tile, xv);
+    enter_tile(tile);
+    int pass = 0;                                    // tiles this block has finished
+    (void)pass;
+    // Phase stamps are taken on the block's fourth tile: a steady-state pass, not the first or last.
+#define STEM_MARK(s) do { if (pass == 3) CVX_TRACE_MARK(s); } while (0)
 
     for (; tile < n_tiles; tile += gridDim.x) {
         const int kb = tile / tiles_per_kb;
@@ -229,25 +262,18 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
         const int p0 = rb * g.TH;
         const int npix = min(g.TH, a.Ho - p0) * a.Wo;
         const bool wave_on = wave < ((npix + 31) >> 5);
+        const bool more = tile + gridDim.x < n_tiles;
 
-        // (1) this tile's patch (in registers since the previous pass) -> LDS; filters if they changed.
-        //     The previous pass has finished reading xs and ws before its last barrier.
-        store_patch(xv);
-        if (kb != cur_kb) {
-            load_filters(k0);
-            cur_kb = kb;
-        }
+        // (1) patch and filters of this tile are in LDS (written before the previous pass's stores)
         __syncthreads();
-        CVX_TRACE_MARK(2);
+        STEM_MARK(2);
 
-        // (2) start fetching the next tile's patch
-        if (tile + gridDim.x < n_tiles) load_patch(tile + gridDim.x, xv);
+        // (2) start fetching the next tile's patch.  No device load is consumed between here and
+        //     (5): one would make the wave wait for this prefetch.
+        if (more) load_patch(tile + gridDim.x, xv);
 
         // (3) multiply.  One k-step = two (channel, filter row) pairs, one per half-wave; the fragments of
         //     step ks+1 are read before the MFMAs of step ks are issued (two register sets).
-        ChannelAffine ca[TN];
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(k0 + tn * 32 + l32, a.K - 1));
         f32x16 acc[TM][TN];
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
@@ -258,6 +284,52 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
                 for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
             }
         if (wave_on) {
+            if constexpr (NKS > 0) {
+                // Straight-line, pinned order: after each MFMA of step ks one fragment of step ks+1 is
+                // read (filters first), so the waits the compiler inserts are partial and the LDS
+                // latency hides behind the matrix pipe.
+                const unsigned char* wl = ws + (size_t)(half * KT + l32) * 16;
+                u32x4 fa[2][TM], fb[2][TN];
+                auto read_a = [&](int tm, int ks) __attribute__((always_inline)) {
+                    const uint32_t* p = (const uint32_t*)(xs + xbase[tm] + rowoff[ks]);   // 4-byte aligned
+                    return u32x4{p[0], p[1], p[2], p[3]};
+                };
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(wl + tn * 32 * 16);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) fa[0][tm] = read_a(tm, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) {
+                    const int b = ks & 1, nb = b ^ 1;
+                    const bool more_k = ks + 1 < NKS;
+                    int issued = 0;
+                    auto read_next = [&]() __attribute__((always_inline)) {
+                        if (issued < TN) fb[nb][issued] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + issued * 32) * 16);
+                        else fa[nb][issued - TN] = read_a(issued - TN, ks + 1);
+                        ++issued;
+                    };
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) {
+                            acc[tm][tn] = stem_mfma<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (more_k && issued < TM + TN) {
+                                read_next();
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < TM + TN; ++j) {
+                        if (more_k && issued < TM + TN) {
+                            read_next();
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                }
+            } else {
             int pr = half;                               // this half-wave's pair index
             int c = 0, r = half;
             while (r >= a.R) { r -= a.R; ++c; }
@@ -296,8 +368,9 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            }
         }
-        CVX_TRACE_MARK(5);
+        STEM_MARK(5);
 
         // (4) epilogue part 1: registers -> LDS as [filter][pixel] in the output type.  The output tile
         //     has its own LDS region; the previous pass's store loop finished reading it before (1).
@@ -327,9 +400,15 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
             else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
         }
         __syncthreads();                             // output tile complete; all reads of xs / ws done
-        CVX_TRACE_MARK(6);
+        STEM_MARK(6);
 
-        // (5) epilogue part 2: the single store, 16 bytes per lane along the pixel axis
+        // (5) the next tile's patch goes into LDS now, BEFORE this tile's stores are issued: loads and
+        //     stores share one in-order counter, so waiting for the patch after the stores would wait
+        //     for the stores to drain as well.
+        if (more) enter_tile(tile + gridDim.x);
+        STEM_MARK(7);
+
+        // (6) epilogue part 2: the single store, 16 bytes per lane along the pixel axis
         {
             constexpr int CH = PT / 8;
             constexpr int RSTEP = THREADS / CH;
@@ -361,8 +440,10 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
                 }
             }
         }
-        CVX_TRACE_MARK(15);
+        STEM_MARK(15);
+        ++pass;
     }
+#undef STEM_MARK
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -372,15 +453,20 @@ constexpr int STEM_LDS_LIMIT = 80 * 1024;     // two blocks per CU
 
 struct StemVariant {
     const char* name;
-    int TM, TN;
+    int TM, TN, NKS;
     void (*kern_bf16)(ConvArgs, StemGeom);
     void (*kern_f16)(ConvArgs, StemGeom);
 };
 
 const StemVariant kStem[] = {
-    {"stem_256x64", 2, 2, stem_kernel<DT_BF16, 2, 2>, stem_kernel<DT_F16, 2, 2>},
-    {"stem_128x64", 1, 2, stem_kernel<DT_BF16, 1, 2>, stem_kernel<DT_F16, 1, 2>},
+    // reduction fully unrolled for 3 channels x 7 filter rows (11 k-steps)
+    {"stem_256x64_k11", 2, 2, 11, stem_kernel<DT_BF16, 2, 2, 11>, stem_kernel<DT_F16, 2, 2, 11>},
+    {"stem_128x64_k11", 1, 2, 11, stem_kernel<DT_BF16, 1, 2, 11>, stem_kernel<DT_F16, 1, 2, 11>},
+    // any C*R: run-time reduction loop
+    {"stem_256x64", 2, 2, 0, stem_kernel<DT_BF16, 2, 2, 0>, stem_kernel<DT_F16, 2, 2, 0>},
+    {"stem_128x64", 1, 2, 0, stem_kernel<DT_BF16, 1, 2, 0>, stem_kernel<DT_F16, 1, 2, 0>},
 };
+constexpr int kNumStem = sizeof(kStem) / sizeof(kStem[0]);
 
 bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
 {
@@ -396,8 +482,11 @@ bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
     if (const char* e = getenv("CVX_STEM_OFF")) {
         if (*e && *e != '0') return false;
     }
+    const char* want = getenv("CVX_STEM_FORCE");                    // developer override: variant name
     for (const StemVariant& v : kStem) {
         const int PT = 4 * v.TM * 32, KT = v.TN * 32;
+        if (want && *want && strcmp(want, v.name) != 0) continue;
+        if (v.NKS > 0 && (a.C * a.R + 1) / 2 != v.NKS) continue;
         if (a.Wo > PT) continue;
         StemGeom g;
         g.TH = PT / a.Wo;
@@ -425,10 +514,7 @@ bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
         g.ph_magic = g.PH > 1 ? (uint32_t)(((1ull << 32) + g.PH - 1) / g.PH) : 0u;
         // prefer the variant that wastes fewer pixel slots
         const int used = g.TH * a.Wo;
-        if (used * 4 < PT * 3 && &v != &kStem[sizeof(kStem) / sizeof(kStem[0]) - 1]) {
-            // try the smaller tile first if this one would be mostly empty
-            continue;
-        }
+        if (used * 4 < PT * 3 && v.TM > 1) continue;       // mostly empty: a smaller tile follows in the table
         *vout = &v;
         *gout = g;
         return true;
@@ -463,7 +549,7 @@ hipError_t launch_stem(const ConvArgs& a, hipStream_t s)
     const int PT = 4 * v->TM * 32, KT = v->TN * 32;
     const int otile = KT * (PT + 8) * 2;
     const int lds = g.xbytes + g.wbytes + otile;
-    static bool raised[2][2];
+    static bool raised[kNumStem][2];
     const int vi = (int)(v - kStem), di = a.dtype == DT_BF16 ? 0 : 1;
     if (!raised[vi][di]) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, STEM_LDS_LIMIT);
@@ -476,6 +562,10 @@ hipError_t launch_stem(const ConvArgs& a, hipStream_t s)
     if (per_cu > 4) per_cu = 4;
     if (per_cu < 1) per_cu = 1;
     long long blocks = 256LL * per_cu;
+    if (const char* e = getenv("CVX_STEM_GRID")) {                  // developer override of the block count
+        const long long v2 = atoll(e);
+        if (v2 > 0) blocks = v2;
+    }
     if (blocks > tiles) blocks = tiles;
     const dim3 grid((unsigned)blocks), block(256);
     hipLaunchKernelGGL(kern, grid, block, lds, s, a, g);
