@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_obj")
 LIB = os.path.join(HERE, "libcvx.so")
-SOURCES = ["cvx_api.cpp", "kernels_direct.hip", "kernels_igemm.hip", "kernels_stem.hip"]
+SOURCES = ["cvx_api.cpp", "kernels_direct.hip", "kernels_igemm.hip", "kernels_stem.hip", "kernels_pointwise.hip"]
 HEADERS = ["cvx_internal.h", "cvx_device.h", os.path.join("..", "..", "include", "cvx.h")]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

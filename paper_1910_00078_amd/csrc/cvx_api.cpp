@@ -136,6 +136,7 @@ cvx_status_t run_conv(cvx_handle_t h, cvx_tensor_desc_t xd, const void* x, cvx_t
     switch (kc.id) {
     case cvx::KID_IGEMM: e = cvx::launch_igemm(a, h->stream); break;
     case cvx::KID_STEM:  e = cvx::launch_stem(a, h->stream); break;
+    case cvx::KID_POINTWISE: e = cvx::launch_pointwise(a, h->stream); break;
     default:             e = cvx::launch_direct(a, h->stream); break;
     }
     if (e != hipSuccess) return fail(CVX_ERR_LAUNCH, "%s: %s", kc.name, hipGetErrorString(e));
@@ -150,6 +151,7 @@ KernelChoice select_kernel(const ConvArgs& a, int policy)
 {
     const char* name = nullptr;
     if (policy == 0) {
+        if (pointwise_supported(a, &name)) return {KID_POINTWISE, name};
         if (stem_supported(a, &name)) return {KID_STEM, name};
         if (igemm_supported(a, &name)) return {KID_IGEMM, name};
     }

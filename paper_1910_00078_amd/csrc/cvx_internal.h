@@ -32,6 +32,7 @@ enum KernelId : int {
     KID_DIRECT = 0,          // one thread per output, any parameters
     KID_IGEMM,               // MFMA implicit GEMM, 16-bit types
     KID_STEM,                // low-channel strided direct-MFMA kernel
+    KID_POINTWISE,           // persistent streaming kernel for 1x1 filters
     KID_COUNT
 };
 
@@ -47,6 +48,8 @@ bool igemm_supported(const ConvArgs& a, const char** variant_name);
 hipError_t launch_igemm(const ConvArgs& a, hipStream_t s);
 bool stem_supported(const ConvArgs& a, const char** variant_name);
 hipError_t launch_stem(const ConvArgs& a, hipStream_t s);
+bool pointwise_supported(const ConvArgs& a, const char** variant_name);
+hipError_t launch_pointwise(const ConvArgs& a, hipStream_t s);
 
 hipError_t launch_bias_add(void* y, const void* bias, int dtype, int bias_f32, int N, int K, int HW, hipStream_t s);
 hipError_t launch_activation(void* y, int dtype, int act, float alpha, long long count, hipStream_t s);

@@ -58,6 +58,13 @@ SMALL = [
     _v("c3a", name="c3a_n2", N=2),
     _v("c3b", name="c3b_n2", N=2),
     _v("c3a", name="1x1_ragged", N=3, C=40, K=24, H=13, W=11),
+    # pointwise kernel: spans that straddle images, ragged K, each tile shape, both 16-bit types
+    _v("c3a", name="pw_k64_straddle", N=5, C=64, K=64, H=12, W=10),
+    _v("c3a", name="pw_k70_two_kblocks", N=3, C=96, K=70, H=20, W=18),
+    _v("c3b", name="pw_k200_c32", N=7, C=32, K=200, H=8, W=8),
+    _v("c3b", name="pw_k128", N=2, C=128, K=128, H=28, W=28),
+    _v("c3a", name="pw_one_chunk", N=1, C=32, K=8, H=2, W=4),
+    _v("c3b", name="pw_f16_c512", N=2, C=512, K=96, H=14, W=12, dtype=wl.F16),
     _v("c3a", name="1x1_stride2", N=2, C=64, K=32, H=15, W=14, stride=(2, 2)),
     _v("c4", name="c4_n2", N=2),
     _v("c4", name="c4_ragged", N=2, H=61, W=45, K=24),
@@ -93,11 +100,23 @@ def test_reduced_shapes_generic_kernel(w):
     check_case(w, policy=1)
 
 
+def test_kernel_families_serve_the_shapes_they_were_built_for():
+    want = {"c2": "igemm_", "c3a": "pointwise_", "c3b": "pointwise_", "c4": "stem_", "c5a": "igemm_", "c5b": "igemm_",
+            "c1": "direct_"}
+    for name, prefix in want.items():
+        w = wl.WORKLOADS[name]
+        plan = cvx.ConvPlan(DT_CODE[w.dtype], (w.N, w.C, w.H, w.W), (w.K, w.C // w.groups, w.R, w.S),
+                            w.pad, w.stride, w.dil, w.groups)
+        got = plan.kernel_name()
+        plan.close()
+        assert got.startswith(prefix), "%s is served by %s" % (name, got)
+
+
 # ---- epilogue variants ----
 @pytest.mark.parametrize("act,alpha", [(cvx.CVX_ACT_IDENTITY, 0.0), (cvx.CVX_ACT_RELU, 0.0),
                                         (cvx.CVX_ACT_LEAKY_RELU, 0.1), (cvx.CVX_ACT_TANH, 0.0),
                                         (cvx.CVX_ACT_LOGISTIC, 0.0)])
-@pytest.mark.parametrize("base", ["c2", "c1", "c4"])
+@pytest.mark.parametrize("base", ["c2", "c1", "c4", "c3a"])
 def test_activations(base, act, alpha):
     w = wl.WORKLOADS[base]
     if base != "c1":
