@@ -626,7 +626,8 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                     if (kl < KT && k0 + kl < a.K) {
                         uint16_t* dst = yg + obase + (size_t)kl * HoWo;
                         if (whole) {
-                            *(u32x4_a2*)dst = v[j];
+                            // streaming store: lines left dirty in L2 would have to be written back at the end of the kernel
+                            __builtin_nontemporal_store(v[j], (u32x4_a2*)dst);
                         } else {
                             // chunk straddles an image boundary or the end of the tile: element-wise
 #pragma unroll

@@ -49,7 +49,7 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 struct Geom {
     int HW;            // pixels per image
     int total_px;      // N * HW
-    int span;          // pixels per block, a multiple of 32
+    int span;          // pixels per block, a multiple of the tile width
     int stages_per_tile;   // C / CC
     int w_off, ca_off, out_off, ring_off;   // LDS byte offsets
 };
@@ -119,6 +119,7 @@ pointwise_kernel(ConvArgs a, Geom g)
     static_assert((NS - 2) * U <= 63, "outstanding loads must fit the counter");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
+    CVX_TRACE_MARK(0);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int HW = g.HW;
@@ -131,6 +132,7 @@ pointwise_kernel(ConvArgs a, Geom g)
     const int n_tiles = (Ge - Gb + PT - 1) / PT;
     const int SPT = g.stages_per_tile;
     const int T = n_tiles * SPT;                                     // stages this block multiplies
+    if (T > 0) CVX_TRACE_MARK(8);
 
     unsigned char* ws = smem + g.w_off;               // written by the multiply waves' prologue
     float* cas = (float*)(smem + g.ca_off);
@@ -141,6 +143,7 @@ pointwise_kernel(ConvArgs a, Geom g)
         // loader waves
         // =========================================================================================
         const int dw = wave - NCW;
+        CVX_TRACE_MARK_T(9, NCW * 64);
         const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
         // LDS position of this lane inside a load: channel row (relative) and 16-byte unit of the row
         const int lane_row = (lane * 16) / ROWB;
@@ -163,6 +166,9 @@ pointwise_kernel(ConvArgs a, Geom g)
             lds_byte* dst = (lds_byte*)(ring + ld_slot * STAGE + dw * 1024);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+#ifdef CVX_EXP_PW_NODMA
+                continue;
+#endif
                 __builtin_amdgcn_global_load_lds((const void*)(src + (long long)u * (ND * RPI) * HW),
                                                  (__attribute__((address_space(3))) void*)(dst + u * ND * 1024), 16, 0, 0);
             }
@@ -172,8 +178,10 @@ pointwise_kernel(ConvArgs a, Geom g)
 
         const int ahead = min(NS - 1, T);
         for (int s = 0; s < ahead; ++s) issue_stage();
+        CVX_TRACE_MARK_T(10, NCW * 64);
         if (ahead == NS - 1) wait_loads_outstanding<(NS - 2) * U>();
         else wait_loads_outstanding<0>();
+        CVX_TRACE_MARK_T(11, NCW * 64);
         stage_barrier();                                             // filters, constants and stage 0 are in LDS
         for (int t = 0; t < T; ++t) {
             // slot (t-1) % NS was multiplied in the previous pass; refill it with stage t+NS-1, then
@@ -206,37 +214,29 @@ pointwise_kernel(ConvArgs a, Geom g)
         unsigned char* ow = smem + g.out_off + wave * (TN * 32 * OPITCH);
 
         // ---- once per block (the loaders are already streaming the input): filters into LDS as
-        //      [channel octet][filter] x 16 bytes, and the epilogue constants.  All device loads of a
-        //      batch are issued before the first is consumed.
+        //      [channel octet][filter] x 16 bytes, by direct-to-LDS loads whose per-lane device address
+        //      does the reordering, and the epilogue constants.  Filter rows past K repeat row K-1:
+        //      they only feed output columns that are never stored.
         {
             const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
-            const int octs = a.C >> 3, units = octs * KT;
-            constexpr int CTHREADS = NCW * 64, WB = 8;
-            for (int base = 0; base < units; base += CTHREADS * WB) {
-                u32x4 wv[WB];
-#pragma unroll
-                for (int i = 0; i < WB; ++i) {
-                    const int u = base + i * CTHREADS + tid;
-                    const int kl = u / octs, o = u - kl * octs;
-                    wv[i] = u32x4{0u, 0u, 0u, 0u};
-                    if (u < units && k0 + kl < a.K) wv[i] = *(const u32x4*)(wg + ((size_t)(k0 + kl) * a.C + o * 8));
-                }
-                if (base == 0) {
-                    for (int kl = tid; kl < KT; kl += CTHREADS) {
-                        const ChannelAffine c1 = channel_affine<DT>(a, min(k0 + kl, a.K - 1));
-                        cas[2 * kl] = c1.mul;
-                        cas[2 * kl + 1] = c1.add;
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < WB; ++i) {
-                    const int u = base + i * CTHREADS + tid;
-                    const int kl = u / octs, o = u - kl * octs;
-                    if (u < units) *(u32x4*)(ws + ((size_t)o * KT + kl) * 16) = wv[i];
-                }
+            constexpr int KCH = KT / 64;                             // 1 KiB chunks per channel octet
+            const int chunks = (a.C >> 3) * KCH;
+            for (int j = wave; j < chunks; j += NCW) {
+                const int o = j / KCH, kl = (j - o * KCH) * 64 + lane;
+                const uint16_t* src = wg + ((size_t)min(k0 + kl, a.K - 1) * a.C + o * 8);
+                __builtin_amdgcn_global_load_lds((const void*)src, (__attribute__((address_space(3))) void*)(lds_byte*)(ws + j * 1024),
+                                                 16, 0, 0);
             }
+            for (int kl = tid; kl < KT; kl += NCW * 64) {
+                const ChannelAffine c1 = channel_affine<DT>(a, min(k0 + kl, a.K - 1));
+                cas[2 * kl] = c1.mul;
+                cas[2 * kl + 1] = c1.add;
+            }
+            wait_loads_outstanding<0>();
         }
+        CVX_TRACE_MARK(1);
         stage_barrier();                                             // filters, constants and stage 0 are in LDS
+        CVX_TRACE_MARK(2);
         ChannelAffine ca[TN];
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
@@ -275,7 +275,9 @@ pointwise_kernel(ConvArgs a, Geom g)
 #pragma unroll
             for (int i = 0; i < TN * 4; ++i) {
                 const int row = i * 8 + (lane >> 3);
-                if (live && k0 + wn * TN * 32 + row < a.K) *(u32x4*)(yg + obase + (size_t)row * HW) = v[i];
+                // streaming store: the output is not read again by this kernel, and lines left dirty in
+                // L2 would all have to be written back at the end of the kernel
+                if (live && k0 + wn * TN * 32 + row < a.K) __builtin_nontemporal_store(v[i], (u32x4*)(yg + obase + (size_t)row * HW));
             }
         };
         auto finish_tile = [&](int tile, auto&& act_fn) __attribute__((always_inline)) {
@@ -296,6 +298,7 @@ pointwise_kernel(ConvArgs a, Geom g)
                             *(u32x2*)(ow + (tn * 32 + l32) * OPITCH + (t2 * 32 + 8 * q4 + 4 * h) * 2) =
                                 u32x2{pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3])};
                         }
+                if (tile == 1) CVX_TRACE_MARK(14);
                 flush_patch(tile, tp);
             }
         };
@@ -305,6 +308,7 @@ pointwise_kernel(ConvArgs a, Geom g)
             const unsigned char* xs = ring + slot * STAGE;
             const unsigned char* wst = wl + (size_t)st * (CC / 8) * KT * 16;
             u32x4 fa[KSTEPS][TM], fb[KSTEPS][TN];
+#ifndef CVX_EXP_PW_NOCOMPUTE
 #pragma unroll
             for (int kk = 0; kk < KSTEPS; ++kk) {
 #pragma unroll
@@ -322,18 +326,23 @@ pointwise_kernel(ConvArgs a, Geom g)
                 for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma<DT>(fa[kk][tm], fb[kk][tn], acc[tm][tn]);
+#endif
 
+            if (st == 0 && tile == 1) CVX_TRACE_MARK(12);
             if (++st == SPT) {
                 st = 0;
+                if (tile == 1) CVX_TRACE_MARK(13);
                 if (a.act == ACT_RELU) finish_tile(tile, [](float v) { return fmaxf(v, 0.0f); });
                 else if (a.act == ACT_IDENTITY) finish_tile(tile, [](float v) { return v; });
                 else finish_tile(tile, [&](float v) { return activate(v, a.act, a.alpha); });
                 seed();
                 ++tile;
+                if (tile <= 6) CVX_TRACE_MARK(2 + tile);
             }
             if (++slot == NS) slot = 0;
             stage_barrier();
         }
+        CVX_TRACE_MARK(15);
     }
 }
 
@@ -384,10 +393,13 @@ bool plan_variant(const ConvArgs& a, const Variant& v, int cus, Plan* out)
     g.ring_off = (int)off;         off += stage * v.NS;
     if (off > LDS_LIMIT) return false;
     const int kblocks = (a.K + KT - 1) / KT;
-    int blocks = cus;
-    long long span = ((long long)g.total_px + blocks - 1) / blocks;
-    span = (span + 31) / 32 * 32;
-    blocks = (int)((g.total_px + span - 1) / span);
+    // Blocks get equal runs of whole tiles: a nearly empty last tile would still cost a block the
+    // full latency of its stages, while leaving a few compute units idle costs nothing as long as
+    // the rest keep device memory busy.
+    const long long tiles = ((long long)g.total_px + PT - 1) / PT;
+    const long long rounds = (tiles + cus - 1) / cus;
+    const long long span = rounds * PT;
+    const int blocks = (int)((g.total_px + span - 1) / span);
     g.span = (int)span;
     out->v = &v;
     out->g = g;
@@ -438,6 +450,13 @@ bool choose(const ConvArgs& a, Plan* out)
 }
 
 }  // namespace pw
+
+#ifdef CVX_PHASE_TRACE
+extern "C" int cvx_debug_set_phase_trace_pointwise(unsigned long long* device_buffer)
+{
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_phase_trace), &device_buffer, sizeof(device_buffer));
+}
+#endif
 
 bool pointwise_supported(const ConvArgs& a, const char** variant_name)
 {

@@ -429,7 +429,8 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
                         if (kl < KT && k0 + kl < a.K) {
                             uint16_t* dst = yg + obase + (size_t)kl * HoWo;
                             if (whole) {
-                                *(u32x4_a2*)dst = v[j];
+                                // streaming store: lines left dirty in L2 would have to be written back at the end of the kernel
+                                __builtin_nontemporal_store(v[j], (u32x4_a2*)dst);
                             } else {
 #pragma unroll
                                 for (int e = 0; e < 8; ++e)
