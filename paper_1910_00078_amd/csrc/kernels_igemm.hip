@@ -763,7 +763,9 @@ double cost(const ConvArgs& a, const Variant& v, const IgemmGeom& g)
     // every wave multiplies all TM of its tiles (dead ones included) unless it has none at all
     const int per_wave = used >= 1 ? v.TM : 0;
     const double mfma = 32.0 * per_wave * v.TN * (a.R * a.S) * (v.CC / 16) * g.n_stages;
-    const double overhead = 6000.0 + 1500.0 * g.n_stages;
+    // fixed launch/drain cost, a barrier hand-over per stage, and the fill of the first stage (which
+    // nothing overlaps): smaller stages start the matrix pipe sooner
+    const double overhead = 3000.0 + 400.0 * g.n_stages + (g.xbytes + g.wbytes) / 16.0;
     const double staged = (double)blocks * g.n_stages * (g.xbytes + g.wbytes) / 256.0 / 64.0;   // 64 B/clk/CU
     return (double)rounds * (mfma + overhead) + staged;
 }

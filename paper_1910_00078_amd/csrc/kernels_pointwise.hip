@@ -51,6 +51,7 @@ struct Geom {
     int total_px;      // N * HW
     int span;          // pixels per block, a multiple of the tile width
     int stages_per_tile;   // C / CC
+    int x_streaming;   // 1: input loads carry the nontemporal hint
     int w_off, ca_off, out_off, ring_off;   // LDS byte offsets
 };
 
@@ -132,7 +133,6 @@ pointwise_kernel(ConvArgs a, Geom g)
     const int n_tiles = (Ge - Gb + PT - 1) / PT;
     const int SPT = g.stages_per_tile;
     const int T = n_tiles * SPT;                                     // stages this block multiplies
-    if (T > 0) CVX_TRACE_MARK(8);
 
     unsigned char* ws = smem + g.w_off;               // written by the multiply waves' prologue
     float* cas = (float*)(smem + g.ca_off);
@@ -143,7 +143,6 @@ pointwise_kernel(ConvArgs a, Geom g)
         // loader waves
         // =========================================================================================
         const int dw = wave - NCW;
-        CVX_TRACE_MARK_T(9, NCW * 64);
         const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
         // LDS position of this lane inside a load: channel row (relative) and 16-byte unit of the row
         const int lane_row = (lane * 16) / ROWB;
@@ -164,13 +163,18 @@ pointwise_kernel(ConvArgs a, Geom g)
             }
             const uint16_t* src = xg + goff + (long long)(ld_st * CC + dw * RPI + lane_row) * HW;
             lds_byte* dst = (lds_byte*)(ring + ld_slot * STAGE + dw * 1024);
+            // The streaming hint keeps a large input from displacing the output lines waiting in L2; it
+            // pays when the input is the larger tensor.
+            if (g.x_streaming) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-#ifdef CVX_EXP_PW_NODMA
-                continue;
-#endif
-                __builtin_amdgcn_global_load_lds((const void*)(src + (long long)u * (ND * RPI) * HW),
-                                                 (__attribute__((address_space(3))) void*)(dst + u * ND * 1024), 16, 0, 0);
+                for (int u = 0; u < U; ++u)
+                    __builtin_amdgcn_global_load_lds((const void*)(src + (long long)u * (ND * RPI) * HW),
+                                                     (__attribute__((address_space(3))) void*)(dst + u * ND * 1024), 16, 0, 2);
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    __builtin_amdgcn_global_load_lds((const void*)(src + (long long)u * (ND * RPI) * HW),
+                                                     (__attribute__((address_space(3))) void*)(dst + u * ND * 1024), 16, 0, 0);
             }
             if (++ld_st == SPT) { ld_st = 0; ++ld_tile; }
             if (++ld_slot == NS) ld_slot = 0;
@@ -298,7 +302,6 @@ pointwise_kernel(ConvArgs a, Geom g)
                             *(u32x2*)(ow + (tn * 32 + l32) * OPITCH + (t2 * 32 + 8 * q4 + 4 * h) * 2) =
                                 u32x2{pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3])};
                         }
-                if (tile == 1) CVX_TRACE_MARK(14);
                 flush_patch(tile, tp);
             }
         };
@@ -308,7 +311,6 @@ pointwise_kernel(ConvArgs a, Geom g)
             const unsigned char* xs = ring + slot * STAGE;
             const unsigned char* wst = wl + (size_t)st * (CC / 8) * KT * 16;
             u32x4 fa[KSTEPS][TM], fb[KSTEPS][TN];
-#ifndef CVX_EXP_PW_NOCOMPUTE
 #pragma unroll
             for (int kk = 0; kk < KSTEPS; ++kk) {
 #pragma unroll
@@ -326,12 +328,9 @@ pointwise_kernel(ConvArgs a, Geom g)
                 for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                     for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma<DT>(fa[kk][tm], fb[kk][tn], acc[tm][tn]);
-#endif
 
-            if (st == 0 && tile == 1) CVX_TRACE_MARK(12);
             if (++st == SPT) {
                 st = 0;
-                if (tile == 1) CVX_TRACE_MARK(13);
                 if (a.act == ACT_RELU) finish_tile(tile, [](float v) { return fmaxf(v, 0.0f); });
                 else if (a.act == ACT_IDENTITY) finish_tile(tile, [](float v) { return v; });
                 else finish_tile(tile, [&](float v) { return activate(v, a.act, a.alpha); });
@@ -383,6 +382,7 @@ bool plan_variant(const ConvArgs& a, const Variant& v, int cus, Plan* out)
     g.HW = a.H * a.W;
     g.total_px = a.N * g.HW;
     g.stages_per_tile = a.C / v.CC;
+    g.x_streaming = a.C > a.K ? 1 : 0;
     const long long wbytes = (long long)a.C * KT * 2;
     const long long stage = (long long)v.CC * PT * 2;
     long long off = 0;
