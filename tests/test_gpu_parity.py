@@ -66,6 +66,15 @@ SMALL = [
     _v("c3a", name="pw_one_chunk", N=1, C=32, K=8, H=2, W=4),
     _v("c3b", name="pw_f16_c512", N=2, C=512, K=96, H=14, W=12, dtype=wl.F16),
     _v("c3a", name="1x1_stride2", N=2, C=64, K=32, H=15, W=14, stride=(2, 2)),
+    # 3x3 unit-stride shapes: image widths 7..64, many small images per tile, ragged K, fp16,
+    # vertical padding / dilation other than 1
+    _v("c2", name="s1_w7_straddle", N=11, C=32, K=64, H=7, W=7),
+    _v("c2", name="s1_w14_k70", N=3, C=48, K=70, H=14, W=14),
+    _v("c2", name="s1_w28_f16", N=2, C=32, K=32, H=28, W=28, dtype=wl.F16),
+    _v("c2", name="s1_w64_h5", N=3, C=16, K=16, H=5, W=64),
+    _v("c2", name="s1_w10_h3_pad0h", N=2, C=16, K=24, H=9, W=10, pad=(0, 1)),
+    _v("c2", name="s1_w20_dilh2", N=2, C=32, K=40, H=11, W=20, pad=(2, 1), dil=(2, 1)),
+    _v("c2", name="s1_w9_padh3", N=1, C=16, K=8, H=4, W=9, pad=(3, 1)),
     _v("c4", name="c4_n2", N=2),
     _v("c4", name="c4_ragged", N=2, H=61, W=45, K=24),
     _v("c4", name="c4_bf16", N=1, H=64, W=64, dtype=wl.BF16),
