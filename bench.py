@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused forward convolution (conv + bias + ReLU) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--all] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--all] [--fusion-sweep] [--no-cpu]
 
 A step is one cvx_conv_fwd_fused call on one batch of synthetic input already resident in HBM.
 Steps rotate over enough disjoint (x, y) buffer sets that the working set exceeds the 256 MiB
@@ -40,14 +40,17 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_workload(name: str, steps: int, warmup: int, check: bool):
+def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = False):
+    """Time one workload (a name from workloads.WORKLOADS, or a ConvWorkload).  `unfused` runs the
+    same operator as three launches -- convolution, bias add, ReLU -- the unfused route of Sec. V."""
     import numpy as np
     import torch
     import workloads as wl
     from paper_1910_00078_amd import cvx
     from parity import to_device, to_host_f64, tolerance_ok, DT_CODE
 
-    w = wl.WORKLOADS[name]
+    w = wl.WORKLOADS[name] if isinstance(name, str) else name
+    name = w.name
     x, wt, b = wl.make_inputs(w)
     stream = torch.cuda.current_stream()
     plan = cvx.ConvPlan(DT_CODE[w.dtype], (w.N, w.C, w.H, w.W), (w.K, w.C // w.groups, w.R, w.S),
@@ -62,7 +65,12 @@ def time_workload(name: str, steps: int, warmup: int, check: bool):
 
     def step(i):
         j = i % nsets
-        plan.run(xs[j].data_ptr(), dw.data_ptr(), db.data_ptr(), ys[j].data_ptr(), cvx.CVX_ACT_RELU, 0.0)
+        if unfused:
+            plan.run_plain(xs[j].data_ptr(), dw.data_ptr(), ys[j].data_ptr())
+            cvx.cvx_bias_add(plan.h, plan.bd, db.data_ptr(), plan.yd, ys[j].data_ptr())
+            cvx.cvx_activation_fwd(plan.h, cvx.CVX_ACT_RELU, 0.0, plan.yd, ys[j].data_ptr())
+        else:
+            plan.run(xs[j].data_ptr(), dw.data_ptr(), db.data_ptr(), ys[j].data_ptr(), cvx.CVX_ACT_RELU, 0.0)
 
     for i in range(max(warmup, 1)):
         step(i)
@@ -134,6 +142,32 @@ def roofline(w, name, ms_kernel):
     return {"bound": bound, "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic}
 
 
+def fusion_sweep(steps: int):
+    """Fused conv+bias+ReLU (one launch) against conv, bias add, ReLU (three launches, two extra
+    passes over the output) on the benchmark layers and on a sweep of the filter count K for a 3x3
+    and a 1x1 layer: the experiment of Fig. 6a of the paper."""
+    import dataclasses
+    import workloads as wl
+    cases = [wl.WORKLOADS[n] for n in ("c2", "c3a", "c3b", "c4", "c5a", "c5b")]
+    for k in (16, 32, 64, 128, 256, 512):
+        cases.append(dataclasses.replace(wl.WORKLOADS["c2"], name="3x3_c64_56x56_k%d" % k, K=k))
+    for k in (16, 64, 256, 1024):
+        cases.append(dataclasses.replace(wl.WORKLOADS["c3a"], name="1x1_c256_56x56_k%d" % k, K=k, N=16))
+    rows = []
+    for w in cases:
+        f = time_workload(w, steps, 3, check=False)
+        u = time_workload(w, steps, 3, check=False, unfused=True)
+        row = {"case": w.name, "K": w.K, "kernel": f["kernel"], "fused_us": f["event_ms_per_step"] * 1e3,
+               "unfused_us": u["event_ms_per_step"] * 1e3,
+               "speedup": u["event_ms_per_step"] / f["event_ms_per_step"]}
+        rows.append(row)
+        log("[fusion] %-24s K=%-5d %-28s fused %8.2f us   conv+bias+relu %8.2f us   x%.2f"
+            % (row["case"], row["K"], row["kernel"], row["fused_us"], row["unfused_us"], row["speedup"]))
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    json.dump(rows, open(os.path.join(ROOT, "gpurun_out", "fusion_sweep.json"), "w"), indent=1)
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -142,6 +176,9 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--all", action="store_true", help="also time every layer; table to stderr and gpurun_out/bench_all.json")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (no parity check, no cpu_baseline)")
+    ap.add_argument("--fusion-sweep", action="store_true",
+                    help="also time fused against unfused (conv, bias add, ReLU as three launches) on every layer and "
+                         "over a sweep of K; table to stderr and gpurun_out/fusion_sweep.json")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run one plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -203,6 +240,9 @@ def main():
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
         json.dump(rows, open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w"), indent=1)
         out["layers"] = rows
+
+    if args.fusion_sweep:
+        out["fusion_sweep"] = fusion_sweep(200)
 
     print(json.dumps(out), flush=True)
 

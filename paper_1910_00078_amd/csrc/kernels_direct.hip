@@ -61,12 +61,42 @@ hipError_t launch_direct(const ConvArgs& a, hipStream_t s)
 }
 
 // ---- unfused element-wise operators --------------------------------------------------------------
+// Each thread handles 16 bytes (8 fp16/bf16 or 4 fp32 elements) per step when y is 16-byte aligned
+// (`vec` = elements per vector, else 1); the bias kernel also needs HW to be a multiple of the
+// vector so that a vector never straddles two channels.  Elements past the last whole vector are
+// done one by one by the first threads.
+typedef uint32_t ew_u32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT, typename F>
+__device__ __forceinline__ void ew_apply_vector(void* y, long long v, F&& f)
+{
+    ew_u32x4 q = ((const ew_u32x4*)y)[v];
+    if constexpr (DT == DT_F32) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) q[e] = __float_as_uint(f(__uint_as_float(q[e])));
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float lo = f(bits16_to_f32<DT>((uint16_t)(q[e] & 0xffffu)));
+            const float hi = f(bits16_to_f32<DT>((uint16_t)(q[e] >> 16)));
+            q[e] = (uint32_t)f32_to_bits16<DT>(lo) | ((uint32_t)f32_to_bits16<DT>(hi) << 16);
+        }
+    }
+    ((ew_u32x4*)y)[v] = q;
+}
+
 template <int DT>
 __global__ void __launch_bounds__(256) bias_add_kernel(void* y, const void* bias, int bias_f32,
-                                                        int K, int HW, long long total)
+                                                        int K, int HW, long long total, int vec)
 {
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x) {
+    const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x, nthreads = (long long)gridDim.x * blockDim.x;
+    const long long nvec = vec > 1 ? total / vec : 0;
+    for (long long v = tid; v < nvec; v += nthreads) {
+        const int k = (int)(((v * vec) / HW) % K);
+        const float b = bias_f32 ? ((const float*)bias)[k] : Elem<DT>::load(bias, k);
+        ew_apply_vector<DT>(y, v, [b](float t) { return t + b; });
+    }
+    for (long long i = nvec * vec + tid; i < total; i += nthreads) {
         const int k = (int)((i / HW) % K);
         const float b = bias_f32 ? ((const float*)bias)[k] : Elem<DT>::load(bias, k);
         Elem<DT>::store(y, (size_t)i, Elem<DT>::load(y, (size_t)i) + b);
@@ -74,11 +104,22 @@ __global__ void __launch_bounds__(256) bias_add_kernel(void* y, const void* bias
 }
 
 template <int DT>
-__global__ void __launch_bounds__(256) activation_kernel(void* y, int act, float alpha, long long total)
+__global__ void __launch_bounds__(256) activation_kernel(void* y, int act, float alpha, long long total, int vec)
 {
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x)
+    const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x, nthreads = (long long)gridDim.x * blockDim.x;
+    const long long nvec = vec > 1 ? total / vec : 0;
+    if (act == ACT_RELU) {
+        for (long long v = tid; v < nvec; v += nthreads) ew_apply_vector<DT>(y, v, [](float t) { return fmaxf(t, 0.0f); });
+    } else {
+        for (long long v = tid; v < nvec; v += nthreads) ew_apply_vector<DT>(y, v, [act, alpha](float t) { return activate(t, act, alpha); });
+    }
+    for (long long i = nvec * vec + tid; i < total; i += nthreads)
         Elem<DT>::store(y, (size_t)i, activate(Elem<DT>::load(y, (size_t)i), act, alpha));
+}
+
+static int ew_vector(const void* y, int dtype)
+{
+    return ((uintptr_t)y & 15) ? 1 : (dtype == DT_F32 ? 4 : 8);
 }
 
 static unsigned ew_blocks(long long total)
@@ -91,11 +132,13 @@ static unsigned ew_blocks(long long total)
 hipError_t launch_bias_add(void* y, const void* bias, int dtype, int bias_f32, int N, int K, int HW, hipStream_t s)
 {
     const long long total = (long long)N * K * HW;
-    const dim3 grid(ew_blocks(total)), block(256);
+    int vec = ew_vector(y, dtype);
+    if (HW % vec) vec = 1;
+    const dim3 grid(ew_blocks(total / vec)), block(256);
     switch (dtype) {
-    case DT_F32:  hipLaunchKernelGGL(bias_add_kernel<DT_F32>, grid, block, 0, s, y, bias, bias_f32, K, HW, total); break;
-    case DT_F16:  hipLaunchKernelGGL(bias_add_kernel<DT_F16>, grid, block, 0, s, y, bias, bias_f32, K, HW, total); break;
-    case DT_BF16: hipLaunchKernelGGL(bias_add_kernel<DT_BF16>, grid, block, 0, s, y, bias, bias_f32, K, HW, total); break;
+    case DT_F32:  hipLaunchKernelGGL(bias_add_kernel<DT_F32>, grid, block, 0, s, y, bias, bias_f32, K, HW, total, vec); break;
+    case DT_F16:  hipLaunchKernelGGL(bias_add_kernel<DT_F16>, grid, block, 0, s, y, bias, bias_f32, K, HW, total, vec); break;
+    case DT_BF16: hipLaunchKernelGGL(bias_add_kernel<DT_BF16>, grid, block, 0, s, y, bias, bias_f32, K, HW, total, vec); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -103,11 +146,12 @@ hipError_t launch_bias_add(void* y, const void* bias, int dtype, int bias_f32, i
 
 hipError_t launch_activation(void* y, int dtype, int act, float alpha, long long total, hipStream_t s)
 {
-    const dim3 grid(ew_blocks(total)), block(256);
+    const int vec = ew_vector(y, dtype);
+    const dim3 grid(ew_blocks(total / vec)), block(256);
     switch (dtype) {
-    case DT_F32:  hipLaunchKernelGGL(activation_kernel<DT_F32>, grid, block, 0, s, y, act, alpha, total); break;
-    case DT_F16:  hipLaunchKernelGGL(activation_kernel<DT_F16>, grid, block, 0, s, y, act, alpha, total); break;
-    case DT_BF16: hipLaunchKernelGGL(activation_kernel<DT_BF16>, grid, block, 0, s, y, act, alpha, total); break;
+    case DT_F32:  hipLaunchKernelGGL(activation_kernel<DT_F32>, grid, block, 0, s, y, act, alpha, total, vec); break;
+    case DT_F16:  hipLaunchKernelGGL(activation_kernel<DT_F16>, grid, block, 0, s, y, act, alpha, total, vec); break;
+    case DT_BF16: hipLaunchKernelGGL(activation_kernel<DT_BF16>, grid, block, 0, s, y, act, alpha, total, vec); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -177,6 +177,45 @@ def test_plain_conv_fwd_and_unfused_operators_agree_with_fused():
     plan.close()
 
 
+@pytest.mark.parametrize("dtype", [wl.F32, wl.F16, wl.BF16])
+@pytest.mark.parametrize("shape,offset", [((2, 5, 4, 8), 0), ((3, 7, 3, 5), 0), ((2, 4, 6, 8), 1), ((1, 3, 1, 1), 0)])
+def test_unfused_bias_add_and_activation_elementwise(dtype, shape, offset):
+    """cvx_bias_add / cvx_activation_fwd on their own against y + b[k] and act(y) in fp64: vector
+    path (aligned, HW a multiple of the vector), scalar path (HW not a multiple, or a base pointer
+    that is only element-aligned) and the tail past the last whole vector."""
+    import torch
+    n, k, h, w_ = shape
+    rng = np.random.default_rng(11)
+    tdt = {wl.F32: torch.float32, wl.F16: torch.float16, wl.BF16: torch.bfloat16}[dtype]
+    count = n * k * h * w_
+    buf = torch.from_numpy(rng.uniform(-2, 2, count + offset).astype(np.float32)).to(tdt).cuda()
+    y = buf[offset:]                                      # offset 1: only element-aligned
+    bias = torch.from_numpy(rng.uniform(-1, 1, k).astype(np.float32)).to(tdt).cuda()
+    y0 = y.double().cpu().numpy().reshape(shape)
+    b0 = bias.double().cpu().numpy()
+    hdl = cvx.cvx_create(torch.cuda.current_stream().cuda_stream)
+    yd, bd = cvx.cvx_tensor_desc_create(), cvx.cvx_tensor_desc_create()
+    cvx.cvx_tensor_desc_set_4d(yd, DT_CODE[dtype], n, k, h, w_)
+    cvx.cvx_tensor_desc_set_4d(bd, DT_CODE[dtype], 1, k, 1, 1)
+    tol = {wl.F32: 1e-6, wl.F16: 2e-3, wl.BF16: 1.6e-2}[dtype]
+    cvx.cvx_bias_add(hdl, bd, bias.data_ptr(), yd, y.data_ptr())
+    torch.cuda.synchronize()
+    want = y0 + b0[None, :, None, None]
+    got = y.double().cpu().numpy().reshape(shape)
+    assert np.all(np.abs(got - want) <= tol * (1 + np.abs(want))), "bias_add"
+    for act, alpha in [(cvx.CVX_ACT_RELU, 0.0), (cvx.CVX_ACT_LEAKY_RELU, 0.25), (cvx.CVX_ACT_TANH, 0.0)]:
+        before = y.double().cpu().numpy().reshape(shape)
+        cvx.cvx_activation_fwd(hdl, act, alpha, yd, y.data_ptr())
+        torch.cuda.synchronize()
+        want = {cvx.CVX_ACT_RELU: np.maximum(before, 0), cvx.CVX_ACT_LEAKY_RELU: np.where(before > 0, before, alpha * before),
+                cvx.CVX_ACT_TANH: np.tanh(before)}[act]
+        got = y.double().cpu().numpy().reshape(shape)
+        assert np.all(np.abs(got - want) <= tol * (1 + np.abs(want))), "activation %d" % act
+    cvx.cvx_tensor_desc_destroy(yd)
+    cvx.cvx_tensor_desc_destroy(bd)
+    cvx.cvx_destroy(hdl)
+
+
 def test_repeated_runs_are_bit_identical():
     import torch
     for name in ("c2", "c3a", "c4", "c5b"):
