@@ -48,7 +48,8 @@ struct IgemmGeom {
     int UPI;         // loader units (8 flat elements x 8 channels) per (octet, image)
     int SLOTS;       // logical LDS elements per (octet, image) = PH * WP
     int PSLOTS;      // physical ones: one spare 16-byte slot after every 8 (see lds_slot)
-    int row_blocks, img_blocks, k_blocks;
+    int row_blocks, img_blocks, k_blocks;   // k_blocks counts the filter blocks of all groups
+    int cg, kg, kb_per_group;              // channels and filters per group (Sec. IV-A grouped convolution); filter blocks per group
     int n_stages;    // ceil(C / CC)
     int a_units;     // input loader units per stage
     int b_units;     // filter loader units per stage (register-transposed path)
@@ -153,7 +154,12 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     const int kb = lid - pb * (int)g.by_kblocks.d;
     const int ib = g.by_rowblocks.d == 1u ? pb : pb / (int)g.by_rowblocks.d;
     const int rb = pb - ib * (int)g.by_rowblocks.d;
-    const int k0 = kb * KT;
+    // grouped convolution: filter block kb belongs to group grp, which reads input channels
+    // [c_first, c_first + cg) and owns filters [k0 .. k_end)
+    const int grp = g.kb_per_group == g.k_blocks ? 0 : kb / g.kb_per_group;
+    const int k0 = grp * g.kg + (kb - grp * g.kb_per_group) * KT;
+    const int k_end = (grp + 1) * g.kg;
+    const int c_first = grp * g.cg;
     const int n0 = ib * g.NB;
     const int p0 = rb * g.TH;
     const int rows = min(g.TH, a.Ho - p0);
@@ -168,7 +174,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
         // =========================================================================================
         const int ptid = tid - NCW * 64;
         const long long x_total = (long long)a.N * a.C * HW;
-        const long long w_total = (long long)a.K * a.C * taps;
+        const long long w_total = (long long)a.K * g.cg * taps;
         const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
         const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
         const int h_lo = p0 * a.stride_h - a.pad_h;    // first input row of the patch (may be < 0)
@@ -193,7 +199,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                 const int img = t - oct * g.NB;
                 a_img[u] = img;
                 a_ui[u] = ui;
-                a_goff[u] = ((long long)(n0 + img) * a.C + oct * 8) * HW + e_lo + ui * 8;
+                a_goff[u] = ((long long)(n0 + img) * a.C + c_first + oct * 8) * HW + e_lo + ui * 8;
                 if (img < nimg) a_oct[u] = oct;        // images past N: nothing to fetch, LDS stays zero
             }
         }
@@ -226,7 +232,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                 if (a_oct[u] >= 0) {
                     const int c0 = cbase + a_oct[u] * 8;
                     const long long off0 = a_goff[u] + (long long)cbase * HW;
-                    const bool fast = off0 >= 0 && off0 + 7LL * HW + 8 <= x_total && c0 + 8 <= a.C;
+                    const bool fast = off0 >= 0 && off0 + 7LL * HW + 8 <= x_total && c0 + 8 <= g.cg;
                     if (fast) {
 #ifdef CVX_EXP_NO_XLOAD
 #pragma unroll
@@ -239,7 +245,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
                             u32x4 v = {0u, 0u, 0u, 0u};
-                            if (c0 + j < a.C) v = load8(xg, off0 + (long long)j * HW, x_total);
+                            if (c0 + j < g.cg) v = load8(xg, off0 + (long long)j * HW, x_total);
                             ra[u][j] = v;
                         }
                     }
@@ -251,8 +257,8 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                     if (b_oct[u] >= 0) {
                         const int k = k0 + b_k[u];
                         const int c0 = cbase + b_oct[u] * 8;
-                        const long long off0 = ((long long)k * a.C + c0) * TAPS;
-                        const bool full = k < a.K && c0 + 8 <= a.C;
+                        const long long off0 = ((long long)k * g.cg + c0) * TAPS;
+                        const bool full = k < k_end && c0 + 8 <= g.cg;
                         if (full) {
 #pragma unroll
                             for (int i = 0; i < BROWS; ++i) {
@@ -272,7 +278,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                                 for (int e = 0; e < 8; ++e) {
                                     const int t = i * 8 + e;          // = j * TAPS + tap
                                     const int j = t / TAPS;
-                                    if (k < a.K && j < 8 && c0 + j < a.C)
+                                    if (k < k_end && j < 8 && c0 + j < g.cg)
                                         v[e >> 1] |= ((uint32_t)wg[off0 + t]) << ((e & 1) * 16);
                                 }
                                 rbv[u][i] = v;
@@ -359,8 +365,8 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                 for (int pi = ptid; pi < KT * CC; pi += PTHREADS) {
                     const int cl = pi % CC, kl = pi / CC;
                     const int k = k0 + kl, c = cbase + cl;
-                    const bool ok = k < a.K && c < a.C;
-                    const long long off0 = ((long long)k * a.C + c) * taps;
+                    const bool ok = k < k_end && c < g.cg;
+                    const long long off0 = ((long long)k * g.cg + c) * taps;
                     for (int t = 0; t < taps; ++t) {
                         const uint16_t v = ok ? wg[off0 + t] : (uint16_t)0;
                         *(uint16_t*)(ws + ((t * OCT + (cl >> 3)) * KT + kl) * 16 + (cl & 7) * 2) = v;
@@ -623,7 +629,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
 #pragma unroll
                 for (int j = 0; j < GRP; ++j) {
                     const int kl = row0 + (p + j) * RSTEP;
-                    if (kl < KT && k0 + kl < a.K) {
+                    if (kl < KT && k0 + kl < k_end) {
                         uint16_t* dst = yg + obase + (size_t)kl * HoWo;
                         if (whole) {
                             // streaming store: lines left dirty in L2 would have to be written back at the end of the kernel
@@ -729,8 +735,11 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     g.PSLOTS = g.SLOTS + g.SLOTS / 8 + 1;
     g.row_blocks = (a.Ho + g.TH - 1) / g.TH;
     g.img_blocks = (a.N + g.NB - 1) / g.NB;
-    g.k_blocks = (a.K + KT - 1) / KT;
-    g.n_stages = (a.C + v.CC - 1) / v.CC;
+    g.cg = a.C / a.groups;
+    g.kg = a.K / a.groups;
+    g.kb_per_group = (g.kg + KT - 1) / KT;
+    g.k_blocks = g.kb_per_group * a.groups;
+    g.n_stages = (g.cg + v.CC - 1) / v.CC;
     const long long a_units = (long long)OCT * g.NB * g.UPI;
     if (a_units > (long long)v.UA * threads) return false;
     g.a_units = (int)a_units;
@@ -792,8 +801,8 @@ bool forced(const ConvArgs& a, const Variant** vout, IgemmGeom* gout)
 bool choose(const ConvArgs& a, const Variant** vout, IgemmGeom* gout)
 {
     if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
-    if (a.groups != 1) return false;
-    if (a.C < 8) return false;                                 // too few channels to fill an octet
+    if (a.groups < 1 || a.C % a.groups || a.K % a.groups) return false;
+    if (a.C / a.groups < 8) return false;                      // too few channels per group to fill an octet
     const long long xbytes = (long long)a.N * a.C * a.H * a.W * 2, ybytes = (long long)a.N * a.K * a.Ho * a.Wo * 2;
     if (xbytes >= (1LL << 31) || ybytes >= (1LL << 31)) return false;
     if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y) & 15) return false;

@@ -91,6 +91,12 @@ SMALL = [
     _v("c2", name="big_pad", N=1, C=8, K=8, H=5, W=6, pad=(4, 5)),
     _v("c2", name="5x5", N=2, C=16, K=32, H=14, W=14, R=5, S=5, pad=(2, 2)),
     _v("c2", name="groups4", N=2, C=32, K=64, H=14, W=14, groups=4),
+    # grouped convolution on the MFMA path: 8 or more channels per group
+    _v("c2", name="groups4_c128_k128", N=3, C=128, K=128, H=14, W=14, groups=4),
+    _v("c2", name="groups2_k96_ragged", N=2, C=64, K=96, H=19, W=17, groups=2),
+    _v("c3a", name="groups4_1x1", N=2, C=64, K=64, H=12, W=12, groups=4),
+    _v("c5b", name="groups8_stride2_f16", N=2, C=128, K=64, H=15, W=15, groups=8, dtype=wl.F16),
+    _v("c2", name="groups3_c40_odd", N=2, C=120, K=24, H=9, W=11, groups=3),
     _v("c2", name="depthwise", N=2, C=32, K=32, H=14, W=14, groups=32),
     _v("c1", name="c1_tiny_1x1img", H=1, W=1, pad=(1, 1)),
     _v("c1", name="c1_C1K1", C=1, K=1),
@@ -119,6 +125,10 @@ def test_kernel_families_serve_the_shapes_they_were_built_for():
         got = plan.kernel_name()
         plan.close()
         assert got.startswith(prefix), "%s is served by %s" % (name, got)
+    grouped = cvx.ConvPlan(DT_CODE[wl.BF16], (2, 128, 14, 14), (128, 32, 3, 3), (1, 1), (1, 1), (1, 1), 4)
+    got = grouped.kernel_name()
+    grouped.close()
+    assert got.startswith("igemm_"), "grouped 3x3 is served by %s" % got
 
 
 # ---- epilogue variants ----
