@@ -475,32 +475,36 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                 auto tap_addr = [&](int tm, int tap) {            // tap is a compile-time constant here
                     return xb[tm][TAPS == 9 ? tap % 3 : 0] + (TAPS == 9 ? tap / 3 : 0) * row_bytes;
                 };
-                u32x4 fa[2][TM], fb[2][TN];
+                // Fragments are read PF k-steps ahead of their MFMAs.  A step of 2x2 tiles is only
+                // 4 MFMAs (128 clocks), shorter than the LDS latency under load, so those variants look
+                // two steps ahead (three register sets); 4x2 tiles cover the latency with one.
+                constexpr int PF = (TM * TN <= 4 && NS >= 3) ? 2 : 1;
+                constexpr int NSET = PF + 1;
+                u32x4 fa[NSET][TM], fb[NSET][TN];
+                auto read_frag = [&](int set, int step, int which) {   // which: 0..TN-1 filters, TN.. pixels
+                    const int tap = step / KSTEPS, kk = step % KSTEPS;
+                    if (which < TN) fb[set][which] = *(const u32x4*)(ws + ((tap * OCT + 2 * kk) * KT + which * 32) * 16);
+                    else fa[set][which - TN] = *(const u32x4*)(xs + tap_addr(which - TN, tap) + 2 * kk * oct_bytes);
+                };
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(ws + tn * 32 * 16);
+                for (int p = 0; p < PF; ++p)
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm) fa[0][tm] = *(const u32x4*)(xs + tap_addr(tm, 0));
+                    for (int j = 0; j < TM + TN; ++j) read_frag(p, p, j);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < NS; ++i) {
-                    const int b = i & 1, nb = b ^ 1;
-                    const bool more = i + 1 < NS;
-                    const int ntap = (i + 1) / KSTEPS, nkk = (i + 1) % KSTEPS;
-                    const int xo = 2 * nkk * oct_bytes;
+                    const int cur = i % NSET, nxt = (i + PF) % NSET;
+                    const bool more = i + PF < NS;
                     int issued = 0;
-                    auto read_next = [&]() {
-                        if (issued < TN) fb[nb][issued] = *(const u32x4*)(ws + ((ntap * OCT + 2 * nkk) * KT + issued * 32) * 16);
-                        else fa[nb][issued - TN] = *(const u32x4*)(xs + tap_addr(issued - TN, ntap) + xo);
-                        ++issued;
-                    };
 #pragma unroll
                     for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
                         for (int tn = 0; tn < TN; ++tn) {
-                            acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
+                            acc[tm][tn] = mfma_32x32x16<DT>(fa[cur][tm], fb[cur][tn], acc[tm][tn]);
                             __builtin_amdgcn_sched_barrier(0);
                             if (more && issued < TM + TN) {
-                                read_next();
+                                read_frag(nxt, i + PF, issued);
+                                ++issued;
                                 __builtin_amdgcn_sched_barrier(0);
                             }
                         }
@@ -508,7 +512,8 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
 #pragma unroll
                     for (int j = 0; j < TM + TN; ++j) {
                         if (more && issued < TM + TN) {
-                            read_next();
+                            read_frag(nxt, i + PF, issued);
+                            ++issued;
                             __builtin_amdgcn_sched_barrier(0);
                         }
                     }
