@@ -448,26 +448,364 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
 }
 
 // ------------------------------------------------------------------------------------------------
+// Streaming arrangement of the same computation, for layers whose filters fit one block (K <= 64):
+// the roles are split so that nothing but one hand-over per tile is block-wide.
+//
+//   loader waves (4)    fetch the input patch of tile i+2 into registers, and write the patch of tile
+//                       i+1 (fetched a tile earlier) into the other of two LDS patch buffers, while
+//                       the multiply waves work on tile i;
+//   multiply waves (8)  64 pixels x 64 filters each: fragments from the current patch buffer and the
+//                       resident filters, MFMA, epilogue in registers, then each wave stages its own
+//                       results through a private LDS patch and stores 128-byte rows itself.  They
+//                       never wait for a device load, and the loaders never wait for a store.
+//
+// LDS map: filters | patch buffer 0 | patch buffer 1 | one output patch [32 filters][64 px + 4] per wave.
+constexpr int STREAM_NCW = 8, STREAM_NLW = 4;   // 12 waves = 3 per SIMD, one block per CU
+constexpr int STREAM_THREADS = (STREAM_NCW + STREAM_NLW) * 64;
+constexpr int STREAM_XU = 5;                  // input loader units per loader thread
+constexpr int STREAM_OPITCH = 136;            // bytes per filter row of an output patch: 64 pixels + 4 (bank spread)
+constexpr int STREAM_PATCH = 32 * STREAM_OPITCH;
+
+template <int DT, int NKS>
+__global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a, StemGeom g)
+{
+    constexpr int TM = 2, TN = 2;
+    constexpr int NCW = STREAM_NCW, THREADS = STREAM_THREADS, LTHREADS = STREAM_NLW * 64;
+    constexpr int PT = NCW * TM * 32;
+    constexpr int KT = TN * 32;
+    constexpr int XU = STREAM_XU;
+    constexpr int WU = 4;
+    constexpr int OPITCH = STREAM_OPITCH;
+    static_assert(NKS > 0, "the streaming arrangement is built for a compile-time reduction length");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    CVX_TRACE_MARK(0);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int HoWo = a.Ho * a.Wo;
+    const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
+    const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
+
+    unsigned char* ws = smem;                                        // filters [pair][KT] x 16 bytes
+    unsigned char* xs0 = smem + g.wbytes;                            // two patch buffers
+    const int n_tiles = a.N * g.row_blocks;                          // one filter block: K <= KT
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int n_my = (n_tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x;   // tiles of this block
+
+    auto bar = []() __attribute__((always_inline)) { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+    // ---- filters, once per block, by all waves: one 16-byte unit per (pair = c*R + r, filter); the
+    //      S <= 8 taps of a filter row are contiguous in w[k][c][r][s]; elements past S are cleared;
+    //      pairs past C*R (the odd one out) and filters past K are zero.
+    {
+        const int per_k = a.C * a.R * a.S;
+        const long long w_total = (long long)a.K * per_k;
+        const int n_wunits = 2 * g.n_ksteps * KT;
+        for (int base = 0; base < n_wunits; base += THREADS * WU) {
+            u32x4 wv[WU];
+#pragma unroll
+            for (int j = 0; j < WU; ++j) {
+                const int ui = base + j * THREADS + tid;
+                wv[j] = u32x4{0u, 0u, 0u, 0u};
+                if (ui < n_wunits) {
+                    const int kl = ui % KT, pair = ui / KT;
+                    if (pair < g.n_pairs && kl < a.K) {
+                        const long long off = (long long)kl * per_k + pair * a.S;
+                        if (off + 8 <= w_total) {
+                            wv[j] = *(const u32x4_a2*)(wg + off);
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e)
+                                if (off + e < w_total) wv[j][e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < WU; ++j) {
+                const int ui = base + j * THREADS + tid;
+                if (ui < n_wunits) {
+                    u32x4 v = wv[j];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                    *(u32x4*)(ws + (size_t)ui * 16) = v;
+                }
+            }
+        }
+    }
+
+    if (wave >= NCW) {
+        // =========================================================================================
+        // loader waves
+        // =========================================================================================
+        const int lt = tid - NCW * 64;
+        const long long x_total = (long long)a.N * a.C * a.H * a.W;
+        // unit u of LDS row rowi = c*PH + patch row covers columns 8u - pad_w .. +7
+        int x_dst[XU], x_c[XU], x_pr[XU], x_col[XU];
+#pragma unroll
+        for (int j = 0; j < XU; ++j) {
+            const int ui = j * LTHREADS + lt;
+            x_dst[j] = -1;
+            x_c[j] = x_pr[j] = x_col[j] = 0;
+            if (ui < g.n_units) {
+                const int rowi = div_small(ui, g.UPR, g.upr_magic);
+                const int u = ui - rowi * g.UPR;
+                x_c[j] = div_small(rowi, g.PH, g.ph_magic);
+                x_pr[j] = rowi - x_c[j] * g.PH;
+                x_col[j] = 8 * u - a.pad_w;
+                x_dst[j] = (rowi * g.WROW + 8 * u) * 2;
+            }
+        }
+        u32x4 xv[XU];
+        // issues the loads of one tile's input patch (nothing here uses a loaded value)
+        auto load_patch = [&](int i) __attribute__((always_inline)) {
+            const int tile = (int)blockIdx.x + i * (int)gridDim.x;
+            const int n = tile / g.row_blocks;
+            const int rb = tile - n * g.row_blocks;
+            const int h_lo = rb * g.TH * a.stride_h - a.pad_h;
+#pragma unroll
+            for (int j = 0; j < XU; ++j) {
+                xv[j] = u32x4{0u, 0u, 0u, 0u};
+                const int h = h_lo + x_pr[j];
+                if (x_dst[j] >= 0 && h >= 0 && h < a.H && x_col[j] < a.W && x_col[j] + 8 > 0) {
+                    const long long off = ((long long)(n * a.C + x_c[j]) * a.H + h) * a.W + x_col[j];
+                    if (off >= 0 && off + 8 <= x_total) {
+                        xv[j] = *(const u32x4_a2*)(xg + off);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const long long o = off + e;
+                            if (o >= 0 && o < x_total) xv[j][e >> 1] |= ((uint32_t)xg[o]) << ((e & 1) * 16);
+                        }
+                    }
+                }
+            }
+        };
+        // clears the columns outside [0, W) (they belong to a neighbouring row, or to nothing) and
+        // writes the patch into patch buffer `buf`
+        auto store_patch = [&](int buf) __attribute__((always_inline)) {
+            unsigned char* xs = xs0 + buf * g.xbytes;
+#pragma unroll
+            for (int j = 0; j < XU; ++j) {
+                if (x_dst[j] >= 0) {
+                    u32x4 v = xv[j];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int col = x_col[j] + e;
+                        if (col < 0 || col >= a.W) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                    }
+                    *(u32x4*)(xs + x_dst[j]) = v;
+                }
+            }
+        };
+        load_patch(0);
+        store_patch(0);
+        if (n_my > 1) load_patch(1);
+        bar();                                                       // filters and the first patch are in LDS
+        for (int i = 0; i < n_my; ++i) {
+            if (i + 1 < n_my) {
+                store_patch((i + 1) & 1);                            // that buffer was multiplied a pass ago
+                if (i + 2 < n_my) load_patch(i + 2);
+            }
+            bar();
+        }
+    } else {
+        // =========================================================================================
+        // multiply waves
+        // =========================================================================================
+        const int l32 = lane & 31, half = lane >> 5;
+        const bool has_bn = a.bn_scale != nullptr;
+        uint16_t* __restrict__ yg = (uint16_t*)a.y;
+        // operand addresses: the wave owns pixels [wave*64, wave*64 + 64) of the tile
+        int xbase[TM];
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int f = (wave * TM + tm) * 32 + l32;
+            const int py = div_small(f, a.Wo, g.wo_magic);
+            const int px = f - py * a.Wo;
+            xbase[tm] = f < g.TH * a.Wo ? ((py * a.stride_h) * g.WROW + px * a.stride_w) * 2 : 0;
+        }
+        int rowoff[NKS];
+        {
+            int c = 0, r = half;
+            while (r >= a.R) { r -= a.R; ++c; }
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                rowoff[ks] = (2 * ks + half) < g.n_pairs ? ((c * g.PH + r) * g.WROW) * 2 : 0;
+                r += 2;
+                while (r >= a.R) { r -= a.R; ++c; }
+            }
+        }
+        ChannelAffine ca[TN];
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(tn * 32 + l32, a.K - 1));
+        unsigned char* ow = smem + g.wbytes + 2 * g.xbytes + wave * STREAM_PATCH;
+        const unsigned char* wl = ws + (size_t)(half * KT + l32) * 16;
+        // identity, ReLU and leaky ReLU are one formula, max(v,0) + slope*min(v,0); tanh and logistic are
+        // applied to the accumulators in a separate pass, after which the formula runs as the identity
+        const bool slow_act = a.act == ACT_TANH || a.act == ACT_LOGISTIC;
+        const float neg_slope = (a.act == ACT_IDENTITY || slow_act) ? 1.0f : (a.act == ACT_LEAKY_RELU ? a.alpha : 0.0f);
+        const bool bn_inline = has_bn && !slow_act;
+
+        bar();                                                       // filters and the first patch are in LDS
+        for (int i = 0; i < n_my; ++i) {
+            const int tile = (int)blockIdx.x + i * (int)gridDim.x;
+            const int n = tile / g.row_blocks;
+            const int rb = tile - n * g.row_blocks;
+            const int p0 = rb * g.TH;
+            const int npix = min(g.TH, a.Ho - p0) * a.Wo;
+            const unsigned char* xs = xs0 + (i & 1) * g.xbytes;
+            const bool wave_on = wave * TM * 32 < npix;
+
+            f32x16 acc[TM][TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const float seed = has_bn ? 0.0f : ca[tn].add;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
+                }
+            if (wave_on) {
+                // straight-line, pinned order: after each MFMA of step ks one fragment of step ks+1 is
+                // read (filters first), so the LDS latency hides behind the matrix pipe
+                u32x4 fa[2][TM], fb[2][TN];
+                auto read_a = [&](int tm, int ks) __attribute__((always_inline)) {
+                    const uint32_t* p = (const uint32_t*)(xs + xbase[tm] + rowoff[ks]);   // 4-byte aligned
+                    return u32x4{p[0], p[1], p[2], p[3]};
+                };
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(wl + tn * 32 * 16);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) fa[0][tm] = read_a(tm, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) {
+                    const int b = ks & 1, nb = b ^ 1;
+                    const bool more_k = ks + 1 < NKS;
+                    int issued = 0;
+                    auto read_next = [&]() __attribute__((always_inline)) {
+                        if (issued < TN) fb[nb][issued] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + issued * 32) * 16);
+                        else fa[nb][issued - TN] = read_a(issued - TN, ks + 1);
+                        ++issued;
+                    };
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn) {
+                            acc[tm][tn] = stem_mfma<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (more_k && issued < TM + TN) {
+                                read_next();
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < TM + TN; ++j) {
+                        if (more_k && issued < TM + TN) {
+                            read_next();
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+                }
+
+                // epilogue: 32 filters at a time through the wave's own patch, then 16 bytes per lane
+                // along the pixel axis (the tile is TH whole output rows: its pixels are contiguous in y)
+                if (slow_act) {
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const float t = acc[tm][tn][r];
+                                acc[tm][tn][r] = activate(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t, a.act, a.alpha);
+                            }
+                }
+                const int P0 = wave * (TM * 32) + (lane & 7) * 8;     // this lane's 8 pixels of the tile
+                const bool any = P0 < npix, whole = P0 + 8 <= npix;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            float v[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                float t = acc[tm][tn][4 * q4 + j];
+                                if (bn_inline) t = fmaf(t, ca[tn].mul, ca[tn].add);
+                                v[j] = fmaf(neg_slope, fminf(t, 0.0f), fmaxf(t, 0.0f));
+                            }
+                            *(uint2*)(ow + l32 * OPITCH + (tm * 32 + 8 * q4 + 4 * half) * 2) =
+                                make_uint2(stem_pack2<DT>(v[0], v[1]), stem_pack2<DT>(v[2], v[3]));
+                        }
+                    u32x4 o[4];
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const unsigned char* p = ow + (r4 * 8 + (lane >> 3)) * OPITCH + (lane & 7) * 16;
+                        const uint2 lo = *(const uint2*)p, hi = *(const uint2*)(p + 8);
+                        o[r4] = u32x4{lo.x, lo.y, hi.x, hi.y};
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    const size_t obase = ((size_t)n * a.K + tn * 32) * HoWo + (size_t)p0 * a.Wo + P0;
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int kl = r4 * 8 + (lane >> 3);
+                        if (any && tn * 32 + kl < a.K) {
+                            uint16_t* dst = yg + obase + (size_t)kl * HoWo;
+                            if (whole) {
+                                // streaming store: lines left dirty in L2 would have to be written back at the end of the kernel
+                                __builtin_nontemporal_store(o[r4], (u32x4_a2*)dst);
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    if (P0 + e < npix) dst[e] = (uint16_t)(o[r4][e >> 1] >> ((e & 1) * 16));
+                            }
+                        }
+                    }
+                }
+            }
+            if (i < 6) CVX_TRACE_MARK(2 + i);
+            bar();
+        }
+        CVX_TRACE_MARK(15);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 namespace {
 
 constexpr int STEM_LDS_LIMIT = 80 * 1024;     // two blocks per CU
+constexpr int STREAM_LDS_LIMIT = 160 * 1024;  // the streaming arrangement runs one block per CU
 
 struct StemVariant {
     const char* name;
     int TM, TN, NKS;
+    int stream;        // 1: streaming arrangement (loader waves + multiply waves), K <= 64
     void (*kern_bf16)(ConvArgs, StemGeom);
     void (*kern_f16)(ConvArgs, StemGeom);
 };
 
 const StemVariant kStem[] = {
+    {"stem_stream_512x64_k11", 2, 2, 11, 1, stem_stream_kernel<DT_BF16, 11>, stem_stream_kernel<DT_F16, 11>},
     // reduction fully unrolled for 3 channels x 7 filter rows (11 k-steps)
-    {"stem_256x64_k11", 2, 2, 11, stem_kernel<DT_BF16, 2, 2, 11>, stem_kernel<DT_F16, 2, 2, 11>},
-    {"stem_128x64_k11", 1, 2, 11, stem_kernel<DT_BF16, 1, 2, 11>, stem_kernel<DT_F16, 1, 2, 11>},
+    {"stem_256x64_k11", 2, 2, 11, 0, stem_kernel<DT_BF16, 2, 2, 11>, stem_kernel<DT_F16, 2, 2, 11>},
+    {"stem_128x64_k11", 1, 2, 11, 0, stem_kernel<DT_BF16, 1, 2, 11>, stem_kernel<DT_F16, 1, 2, 11>},
     // any C*R: run-time reduction loop
-    {"stem_256x64", 2, 2, 0, stem_kernel<DT_BF16, 2, 2, 0>, stem_kernel<DT_F16, 2, 2, 0>},
-    {"stem_128x64", 1, 2, 0, stem_kernel<DT_BF16, 1, 2, 0>, stem_kernel<DT_F16, 1, 2, 0>},
+    {"stem_256x64", 2, 2, 0, 0, stem_kernel<DT_BF16, 2, 2, 0>, stem_kernel<DT_F16, 2, 2, 0>},
+    {"stem_128x64", 1, 2, 0, 0, stem_kernel<DT_BF16, 1, 2, 0>, stem_kernel<DT_F16, 1, 2, 0>},
 };
 constexpr int kNumStem = sizeof(kStem) / sizeof(kStem[0]);
+
+int stem_lds(const StemVariant& v, const StemGeom& g)
+{
+    if (v.stream) return g.wbytes + 2 * g.xbytes + STREAM_NCW * STREAM_PATCH;
+    const int PT = 4 * v.TM * 32, KT = v.TN * 32;
+    return g.xbytes + g.wbytes + KT * (PT + 8) * 2;
+}
 
 bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
 {
@@ -485,7 +823,7 @@ bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
     }
     const char* want = getenv("CVX_STEM_FORCE");                    // developer override: variant name
     for (const StemVariant& v : kStem) {
-        const int PT = 4 * v.TM * 32, KT = v.TN * 32;
+        const int PT = (v.stream ? STREAM_NCW : 4) * v.TM * 32, KT = v.TN * 32;
         if (want && *want && strcmp(want, v.name) != 0) continue;
         if (v.NKS > 0 && (a.C * a.R + 1) / 2 != v.NKS) continue;
         if (a.Wo > PT) continue;
@@ -505,10 +843,12 @@ bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
         g.k_blocks = (a.K + KT - 1) / KT;
         g.xbytes = a.C * g.PH * g.WROW * 2;
         g.wbytes = 2 * g.n_ksteps * KT * 16;
-        const int otile = KT * (PT + 8) * 2;
-        const int lds = g.xbytes + g.wbytes + otile;
-        if (lds > STEM_LDS_LIMIT) continue;
-        if (g.n_units > 4 * 256) continue;                         // 4 loader units per thread
+        if (stem_lds(v, g) > (v.stream ? STREAM_LDS_LIMIT : STEM_LDS_LIMIT)) continue;
+        if (v.stream) {
+            if (g.k_blocks != 1 || g.n_units > STREAM_XU * STREAM_NLW * 64) continue;
+        } else if (g.n_units > 4 * 256) {
+            continue;                                              // 4 loader units per thread
+        }
         if ((long long)a.N * g.row_blocks * g.k_blocks > 0x7fffffffLL) continue;
         g.wo_magic = a.Wo > 1 ? (uint32_t)(((1ull << 32) + a.Wo - 1) / a.Wo) : 0u;
         g.upr_magic = g.UPR > 1 ? (uint32_t)(((1ull << 32) + g.UPR - 1) / g.UPR) : 0u;
@@ -547,13 +887,11 @@ hipError_t launch_stem(const ConvArgs& a, hipStream_t s)
     StemGeom g;
     if (!stem_plan(a, &v, &g)) return hipErrorInvalidValue;
     auto kern = a.dtype == DT_BF16 ? v->kern_bf16 : v->kern_f16;
-    const int PT = 4 * v->TM * 32, KT = v->TN * 32;
-    const int otile = KT * (PT + 8) * 2;
-    const int lds = g.xbytes + g.wbytes + otile;
+    const int lds = stem_lds(*v, g);
     static bool raised[kNumStem][2];
     const int vi = (int)(v - kStem), di = a.dtype == DT_BF16 ? 0 : 1;
     if (!raised[vi][di]) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, STEM_LDS_LIMIT);
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, v->stream ? STREAM_LDS_LIMIT : STEM_LDS_LIMIT);
         if (e != hipSuccess) return e;
         raised[vi][di] = true;
     }
@@ -568,7 +906,7 @@ hipError_t launch_stem(const ConvArgs& a, hipStream_t s)
         if (v2 > 0) blocks = v2;
     }
     if (blocks > tiles) blocks = tiles;
-    const dim3 grid((unsigned)blocks), block(256);
+    const dim3 grid((unsigned)blocks), block(v->stream ? STREAM_THREADS : 256);
     hipLaunchKernelGGL(kern, grid, block, lds, s, a, g);
     return hipGetLastError();
 }
