@@ -494,47 +494,6 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
 
     auto bar = []() __attribute__((always_inline)) { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-    // ---- filters, once per block, by all waves: one 16-byte unit per (pair = c*R + r, filter); the
-    //      S <= 8 taps of a filter row are contiguous in w[k][c][r][s]; elements past S are cleared;
-    //      pairs past C*R (the odd one out) and filters past K are zero.
-    {
-        const int per_k = a.C * a.R * a.S;
-        const long long w_total = (long long)a.K * per_k;
-        const int n_wunits = 2 * g.n_ksteps * KT;
-        for (int base = 0; base < n_wunits; base += THREADS * WU) {
-            u32x4 wv[WU];
-#pragma unroll
-            for (int j = 0; j < WU; ++j) {
-                const int ui = base + j * THREADS + tid;
-                wv[j] = u32x4{0u, 0u, 0u, 0u};
-                if (ui < n_wunits) {
-                    const int kl = ui % KT, pair = ui / KT;
-                    if (pair < g.n_pairs && kl < a.K) {
-                        const long long off = (long long)kl * per_k + pair * a.S;
-                        if (off + 8 <= w_total) {
-                            wv[j] = *(const u32x4_a2*)(wg + off);
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (off + e < w_total) wv[j][e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
-                        }
-                    }
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < WU; ++j) {
-                const int ui = base + j * THREADS + tid;
-                if (ui < n_wunits) {
-                    u32x4 v = wv[j];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                    *(u32x4*)(ws + (size_t)ui * 16) = v;
-                }
-            }
-        }
-    }
-
     if (wave >= NCW) {
         // =========================================================================================
         // loader waves
@@ -601,8 +560,8 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
         };
         load_patch(0);
         store_patch(0);
-        if (n_my > 1) load_patch(1);
         bar();                                                       // filters and the first patch are in LDS
+        if (n_my > 1) load_patch(1);
         for (int i = 0; i < n_my; ++i) {
             if (i + 1 < n_my) {
                 store_patch((i + 1) & 1);                            // that buffer was multiplied a pass ago
@@ -635,6 +594,46 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
                 rowoff[ks] = (2 * ks + half) < g.n_pairs ? ((c * g.PH + r) * g.WROW) * 2 : 0;
                 r += 2;
                 while (r >= a.R) { r -= a.R; ++c; }
+            }
+        }
+        // ---- filters, once per block, by the multiply waves (the loaders are already fetching the first
+        //      patch): one 16-byte unit per (pair = c*R + r, filter); the S <= 8 taps of a filter row are contiguous in w[k][c][r][s]; elements past S are cleared;
+        //      pairs past C*R (the odd one out) and filters past K are zero.
+        {
+            const int per_k = a.C * a.R * a.S;
+            const long long w_total = (long long)a.K * per_k;
+            const int n_wunits = 2 * g.n_ksteps * KT;
+            for (int base = 0; base < n_wunits; base += NCW * 64 * WU) {
+                u32x4 wv[WU];
+#pragma unroll
+                for (int j = 0; j < WU; ++j) {
+                    const int ui = base + j * (NCW * 64) + tid;
+                    wv[j] = u32x4{0u, 0u, 0u, 0u};
+                    if (ui < n_wunits) {
+                        const int kl = ui % KT, pair = ui / KT;
+                        if (pair < g.n_pairs && kl < a.K) {
+                            const long long off = (long long)kl * per_k + pair * a.S;
+                            if (off + 8 <= w_total) {
+                                wv[j] = *(const u32x4_a2*)(wg + off);
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 8; ++e)
+                                    if (off + e < w_total) wv[j][e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < WU; ++j) {
+                    const int ui = base + j * (NCW * 64) + tid;
+                    if (ui < n_wunits) {
+                        u32x4 v = wv[j];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                        *(u32x4*)(ws + (size_t)ui * 16) = v;
+                    }
+                }
             }
         }
         ChannelAffine ca[TN];
