@@ -118,14 +118,27 @@ __device__ __forceinline__ int lds_slot(int s) { return s + (s >> 3); }
 // while the consumers multiply stage s.  One consumer and one producer wave share each SIMD, so the
 // producers' vector-ALU and memory work runs in the shadow of the matrix pipe.  One s_barrier per
 // stage hands a finished buffer from producers to consumers and a drained one back.
+// 8: four producer waves for the input and four for the filters; 4: four that do both (kernels whose
+// registers do not allow three waves per SIMD: 4x2 register tiles, or several 3x3 loader units per thread).
+__host__ __device__ constexpr int igemm_producer_waves(int TM, int TN, int TAPS, int UA, int UB)
+{
+    return (TM * TN <= 4 && !(TAPS == 9 && (UA > 1 || UB > 1))) ? 8 : 4;
+}
+
 template <int DT, int WM, int WN, int TM, int TN, int CC, int TAPS, int UA, int UB>
-__global__ void __launch_bounds__((WM * WN + 4) * 64)
+__global__ void __launch_bounds__((WM * WN + igemm_producer_waves(TM, TN, TAPS, UA, UB)) * 64)
 igemm_kernel(ConvArgs a, IgemmGeom g)
 {
     constexpr int NCW = WM * WN;           // consumer waves
-    constexpr int NPW = 4;                 // producer waves
+    // Producer waves.  Kernels with 2x2 register tiles leave room for twelve waves per block (three per
+    // SIMD, 168 registers each): four producer waves load the input and four more the filters, which
+    // halves each producer's chain of loads, transposes and LDS writes per stage.  The 4x2 kernels
+    // need the registers (two waves per SIMD) and keep four producer waves that do both.
+    constexpr int NPW = igemm_producer_waves(TM, TN, TAPS, UA, UB);
+    constexpr bool SPLIT = NPW == 8;
     constexpr int THREADS = (NCW + NPW) * 64;
-    constexpr int PTHREADS = NPW * 64;
+    constexpr int PTHREADS = NPW * 64;     // all producer threads (zero fill)
+    constexpr int UTHREADS = 4 * 64;       // threads that share the units of one kind
     constexpr int KT = WN * TN * 32;       // filters per block   (MFMA B operand / D columns)
     constexpr int PT = WM * TM * 32;       // pixels per block    (MFMA A operand / D rows)
     constexpr int OCT = CC / 8;
@@ -173,6 +186,9 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
         // producer waves
         // =========================================================================================
         const int ptid = tid - NCW * 64;
+        const bool input_wave = !SPLIT || wave < NCW + 4;          // wave-uniform role among the producers
+        const bool filter_wave = !SPLIT || wave >= NCW + 4;
+        const int utid = (SPLIT && !input_wave) ? ptid - UTHREADS : ptid;
         const long long x_total = (long long)a.N * a.C * HW;
         const long long w_total = (long long)a.K * g.cg * taps;
         const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
@@ -187,12 +203,12 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
         int a_oct[UA], a_img[UA], a_ui[UA];
 #pragma unroll
         for (int u = 0; u < UA; ++u) {
-            const int ua = ptid + u * PTHREADS;
+            const int ua = utid + u * UTHREADS;
             a_oct[u] = -1;
             a_goff[u] = 0;
             a_img[u] = 0;
             a_ui[u] = 0;
-            if (ua < g.a_units) {
+            if (input_wave && ua < g.a_units) {
                 const int t = g.by_upi.div(ua);
                 const int ui = ua - t * g.UPI;
                 const int oct = g.by_nb.div(t);
@@ -207,10 +223,10 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
         int b_k[UB], b_oct[UB];
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
-            const int ub = ptid + u * PTHREADS;
+            const int ub = utid + u * UTHREADS;
             b_k[u] = ub % KT;
             b_oct[u] = ub / KT;
-            if (ub >= g.b_units) b_oct[u] = -1;
+            if (!filter_wave || ub >= g.b_units) b_oct[u] = -1;
         }
 
         // Two register sets: the loads of two stages are in flight at once, so a stage's data has
@@ -362,7 +378,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             } else {
                 // any filter size: element-wise gather from global memory, scatter into LDS
                 const int cbase = st * CC;
-                for (int pi = ptid; pi < KT * CC; pi += PTHREADS) {
+                for (int pi = filter_wave ? utid : KT * CC; pi < KT * CC; pi += UTHREADS) {
                     const int cl = pi % CC, kl = pi / CC;
                     const int k = k0 + kl, c = cbase + cl;
                     const bool ok = k < k_end && c < g.cg;
@@ -869,7 +885,7 @@ hipError_t launch_igemm(const ConvArgs& a, hipStream_t s)
         if (e != hipSuccess) return e;
         raised[vi][di] = true;
     }
-    const dim3 grid((unsigned)(g.row_blocks * g.img_blocks * g.k_blocks)), block((v->WM * v->WN + 4) * 64);
+    const dim3 grid((unsigned)(g.row_blocks * g.img_blocks * g.k_blocks)), block((v->WM * v->WN + igemm_producer_waves(v->TM, v->TN, v->TAPS, v->UA, v->UB)) * 64);
     hipLaunchKernelGGL(kern, grid, block, lds, s, a, g);
     return hipGetLastError();
 }
