@@ -151,6 +151,33 @@ def test_stream_roundtrip_and_query():
     assert ws == 0 and name
 
 
+def test_kernel_choice_is_host_logic_and_follows_the_shape():
+    """cvx_conv_fwd_query needs no GPU: the choice of kernel family is a pure function of the
+    descriptors.  The benchmark layers and a few neighbours land where they were built to."""
+    import workloads as wl
+    code = {wl.F32: cvx.CVX_F32, wl.F16: cvx.CVX_F16, wl.BF16: cvx.CVX_BF16}
+
+    def family(w):
+        plan = cvx.ConvPlan(code[w.dtype], (w.N, w.C, w.H, w.W), (w.K, w.C // w.groups, w.R, w.S),
+                            w.pad, w.stride, w.dil, w.groups)
+        try:
+            return plan.kernel_name()
+        finally:
+            plan.close()
+
+    want = {"c1": "direct_", "c2": "igemm_", "c3a": "pointwise_", "c3b": "pointwise_", "c4": "stem_stream_",
+            "c5a": "igemm_", "c5b": "igemm_"}
+    for name, prefix in want.items():
+        assert family(wl.WORKLOADS[name]).startswith(prefix), name
+    v = wl.small_variant
+    assert family(v(wl.WORKLOADS["c4"], K=96)).startswith("stem_256x64")            # K > 64: the general stem kernel
+    assert family(v(wl.WORKLOADS["c3a"], stride=(2, 2))).startswith("igemm_")        # strided 1x1 is not pointwise
+    assert family(v(wl.WORKLOADS["c3a"], H=7, W=7)).startswith("igemm_")             # 49 pixels: not a multiple of 8
+    assert family(v(wl.WORKLOADS["c2"], C=128, K=128, groups=4)).startswith("igemm_")
+    assert family(v(wl.WORKLOADS["c2"], C=64, K=64, groups=64)).startswith("direct_")  # depthwise
+    assert family(v(wl.WORKLOADS["c2"], dtype=wl.F32)).startswith("direct_")
+
+
 def test_out_params_untouched_on_failure():
     L = cvx.lib()
     h = ctypes.c_void_p(0xdead)
