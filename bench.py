@@ -29,10 +29,11 @@ PEAK_MFMA_16BIT_TFLOPS = 2516.6      # dense bf16 / fp16 MFMA
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 ROTATE_BYTES = 1 << 30               # rotate buffer sets over at least this much memory
+RESULTS_DIR = os.path.join(ROOT, "gpurun_out")   # where the per-layer tables are written as JSON
 GRAPH_CHUNK = 250
 
-# Which roofline binds each layer (arithmetic intensity against the 315 FLOP/byte ridge point,
-# see the design doc): the two 1x1 layers and the stem are HBM-bound, the 3x3 layers MFMA-bound.
+# Which roofline binds each layer (arithmetic intensity against the ridge point of 2516.6 TFLOP/s over
+# 8 TB/s = 315 FLOP/byte): the two 1x1 layers and the stem are HBM-bound, the 3x3 layers MFMA-bound.
 BOUND = {"c1": "alu", "c2": "mfma", "c3a": "hbm", "c3b": "hbm", "c4": "hbm", "c5a": "mfma", "c5b": "mfma"}
 
 
@@ -163,8 +164,8 @@ def fusion_sweep(steps: int):
         rows.append(row)
         log("[fusion] %-24s K=%-5d %-28s fused %8.2f us   conv+bias+relu %8.2f us   x%.2f"
             % (row["case"], row["K"], row["kernel"], row["fused_us"], row["unfused_us"], row["speedup"]))
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    json.dump(rows, open(os.path.join(ROOT, "gpurun_out", "fusion_sweep.json"), "w"), indent=1)
+    os.makedirs(RESULTS_DIR, exist_ok=True)
+    json.dump(rows, open(os.path.join(RESULTS_DIR, "fusion_sweep.json"), "w"), indent=1)
     return rows
 
 
@@ -174,18 +175,18 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2")
-    ap.add_argument("--all", action="store_true", help="also time every layer; table to stderr and gpurun_out/bench_all.json")
+    ap.add_argument("--all", action="store_true", help="also time every layer; table to stderr and bench_all.json in the results directory")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (no parity check, no cpu_baseline)")
     ap.add_argument("--fusion-sweep", action="store_true",
                     help="also time fused against unfused (conv, bias add, ReLU as three launches) on every layer and "
-                         "over a sweep of K; table to stderr and gpurun_out/fusion_sweep.json")
+                         "over a sweep of K; table to stderr and fusion_sweep.json in the results directory")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="first run one plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (forward convolution shards over the batch with no "
-              "communication; see DESIGN.md); --gpus %d is not available" % args.gpus, file=sys.stderr)
+              "communication: each GPU would take a slice of the images and a copy of the filters); --gpus %d is not available" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
@@ -237,8 +238,8 @@ def main():
             rows.append(row)
             log("[bench] %-4s %-28s %9.2f us  %8.1f TFLOP/s  %8.1f GB/s  %s frac %.3f"
                 % (name, row["kernel"], row["us"], row["tflops"], row["gbs"], row["bound"], row["frac"]))
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        json.dump(rows, open(os.path.join(ROOT, "gpurun_out", "bench_all.json"), "w"), indent=1)
+        os.makedirs(RESULTS_DIR, exist_ok=True)
+        json.dump(rows, open(os.path.join(RESULTS_DIR, "bench_all.json"), "w"), indent=1)
         out["layers"] = rows
 
     if args.fusion_sweep:
