@@ -701,6 +701,7 @@ struct Variant {
 const Variant kVariants[] = {
     IGEMM_VARIANT("igemm_512x64_c32_3x3", 4, 1, 4, 2, 32, 9, 1, 1),
     IGEMM_VARIANT("igemm_512x64_c16_3x3", 4, 1, 4, 2, 16, 9, 1, 1),
+    IGEMM_VARIANT("igemm_256x128_c16_3x3", 4, 1, 2, 4, 16, 9, 1, 1),
     IGEMM_VARIANT("igemm_256x64_c32_3x3", 4, 1, 2, 2, 32, 9, 1, 1),
     IGEMM_VARIANT("igemm_256x64_c16_3x3", 4, 1, 2, 2, 16, 9, 1, 1),
     IGEMM_VARIANT("igemm_256x64_c16_3x3_u2", 4, 1, 2, 2, 16, 9, 2, 1),

@@ -84,6 +84,8 @@ SMALL = [
     _v("c4", name="stem_narrow", N=3, C=3, H=9, W=9, K=5),
     _v("c5a", name="c5a_small", N=6, C=64, K=96),
     _v("c5b", name="c5b_small", N=3, C=64, K=48),
+    _v("c5b", name="c5b_k256_wide_filter_tile", N=3, C=32),
+    _v("c5b", name="c5b_k200_ragged_filter_tile", N=2, C=48, K=200),
     _v("c5b", name="c5b_odd", N=2, C=32, K=32, H=27, W=25),
     _v("c2", name="dil2", N=2, C=32, K=32, H=20, W=18, pad=(2, 2), dil=(2, 2)),
     _v("c2", name="rect_filter", N=2, C=16, K=16, H=17, W=21, R=3, S=5, pad=(1, 2)),
