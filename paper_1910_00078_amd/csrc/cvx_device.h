@@ -96,6 +96,45 @@ __device__ __forceinline__ float finish(float acc, const ChannelAffine& ca, bool
     return activate(v, act, alpha);
 }
 
+// The bias + ReLU (or identity) epilogue on values already rounded to bf16 / fp16 and packed two to
+// a dword.  Both formats are sign-magnitude, so as signed 16-bit integers the negative values are
+// exactly the negative integers: max(v, 0) is ReLU, max(v, -32768) the identity, one v_pk_max_i16 for
+// two values.  Rounding before the ReLU gives the same result as after it (rounding keeps the sign).
+typedef short s16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t packed_floor(bool relu)
+{
+    return relu ? 0u : 0x80008000u;
+}
+__device__ __forceinline__ uint32_t max_packed(uint32_t v, uint32_t floor2)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, v), __builtin_bit_cast(s16x2_t, floor2)));
+}
+
+// Fetches the first BYTES bytes of the kernel-argument segment with a few wide scalar loads that
+// are all in flight together, and waits for them once.  The compiler otherwise fetches arguments
+// where they are first needed, and a kernel prologue that decodes its tile from several of them
+// then pays the (cold) argument-memory latency several times in a row; after this call every later
+// argument fetch hits the scalar cache.  BYTES must not exceed the size of the explicit arguments.
+template <int BYTES>
+__device__ __forceinline__ void warm_kernel_arguments()
+{
+    typedef uint32_t u32x16_s __attribute__((ext_vector_type(16)));
+    typedef const __attribute__((address_space(4))) uint32_t* karg_ptr;
+    typedef const __attribute__((address_space(4))) u32x16_s* karg16_ptr;
+    const karg_ptr ka = (karg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    // one 64-byte load per cache line of the arguments; a single asm statement takes all results, so
+    // the loads are issued back to back and waited for together
+    constexpr int N16 = BYTES / 64;
+    static_assert(N16 >= 1 && N16 <= 5, "argument block size not covered");
+    const karg16_ptr k16 = (karg16_ptr)ka;
+    const uint32_t last = ka[BYTES / 4 - 1];      // the line holding the tail of the arguments
+    if constexpr (N16 == 1) asm volatile("" ::"s"(k16[0]), "s"(last));
+    if constexpr (N16 == 2) asm volatile("" ::"s"(k16[0]), "s"(k16[1]), "s"(last));
+    if constexpr (N16 == 3) asm volatile("" ::"s"(k16[0]), "s"(k16[1]), "s"(k16[2]), "s"(last));
+    if constexpr (N16 == 4) asm volatile("" ::"s"(k16[0]), "s"(k16[1]), "s"(k16[2]), "s"(k16[3]), "s"(last));
+    if constexpr (N16 == 5) asm volatile("" ::"s"(k16[0]), "s"(k16[1]), "s"(k16[2]), "s"(k16[3]), "s"(k16[4]), "s"(last));
+}
+
 // Developer facility, compiled out unless CVX_PHASE_TRACE is defined: thread 0 of every block
 // records wall-clock timestamps (100 MHz) at phase boundaries into a caller-provided buffer of
 // 32 slots per block (16 wall-clock stamps, then 16 shader-clock stamps).

@@ -10,6 +10,7 @@ namespace cvx {
 template <int DT>
 __global__ void __launch_bounds__(256) direct_conv_kernel(ConvArgs a)
 {
+    warm_kernel_arguments<sizeof(ConvArgs)>();
     const long long total = (long long)a.N * a.K * a.Ho * a.Wo;
     const int cg = a.C / a.groups;
     const int kg = a.K / a.groups;

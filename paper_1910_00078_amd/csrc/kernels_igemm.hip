@@ -148,6 +148,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     constexpr int BUF0 = 16;
 
     CVX_TRACE_MARK(0);
+    warm_kernel_arguments<sizeof(ConvArgs) + sizeof(IgemmGeom)>();
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
     const bool producer = wave >= NCW;
@@ -614,7 +615,25 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                     }
                 }
             };
-            if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
+            if ((a.act == ACT_RELU || a.act == ACT_IDENTITY) && !has_bn) {
+                // the common case (the bias is already in the accumulators), kept short because only the
+                // consumer waves can do it: round, then ReLU on the packed pair, 1 instruction per value
+                const uint32_t floor2 = packed_floor(a.act == ACT_RELU);
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) {
+                    const int kl = (wn * TN + tn) * 32 + l32;
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const f32x16& t = acc[tm][tn];
+                            const int f = (tm * WM + wm) * 32 + 8 * q4 + 4 * half;
+                            *(uint2*)(ot + kl * PTP + f) = make_uint2(max_packed(pack2<DT>(t[4 * q4], t[4 * q4 + 1]), floor2),
+                                                                      max_packed(pack2<DT>(t[4 * q4 + 2], t[4 * q4 + 3]), floor2));
+                        }
+                    }
+                }
+            } else if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
             else if (a.act == ACT_IDENTITY) stage_out([](float t) { return t; });
             else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
         }

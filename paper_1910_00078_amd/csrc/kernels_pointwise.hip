@@ -121,6 +121,7 @@ pointwise_kernel(ConvArgs a, Geom g)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     CVX_TRACE_MARK(0);
+    warm_kernel_arguments<sizeof(ConvArgs) + sizeof(Geom)>();
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int HW = g.HW;
@@ -306,6 +307,26 @@ pointwise_kernel(ConvArgs a, Geom g)
             }
         };
 
+        // bias + ReLU / identity (the bias is already in the accumulators): round, then ReLU on the
+        // packed pair, 1 instruction per value
+        auto finish_tile_packed = [&](int tile, uint32_t floor2) __attribute__((always_inline)) {
+#pragma unroll
+            for (int tp = 0; tp < TM / 2; ++tp) {
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) {
+                            const auto& t = acc[tp * 2 + t2][tn];
+                            *(u32x2*)(ow + (tn * 32 + l32) * OPITCH + (t2 * 32 + 8 * q4 + 4 * h) * 2) =
+                                u32x2{max_packed(pack2<DT>(t[4 * q4], t[4 * q4 + 1]), floor2),
+                                      max_packed(pack2<DT>(t[4 * q4 + 2], t[4 * q4 + 3]), floor2)};
+                        }
+                flush_patch(tile, tp);
+            }
+        };
+
         int st = 0, tile = 0, slot = 0;
         for (int t = 0; t < T; ++t) {
             const unsigned char* xs = ring + slot * STAGE;
@@ -331,7 +352,8 @@ pointwise_kernel(ConvArgs a, Geom g)
 
             if (++st == SPT) {
                 st = 0;
-                if (a.act == ACT_RELU) finish_tile(tile, [](float v) { return fmaxf(v, 0.0f); });
+                if (!has_bn && (a.act == ACT_RELU || a.act == ACT_IDENTITY)) finish_tile_packed(tile, packed_floor(a.act == ACT_RELU));
+                else if (a.act == ACT_RELU) finish_tile(tile, [](float v) { return fmaxf(v, 0.0f); });
                 else if (a.act == ACT_IDENTITY) finish_tile(tile, [](float v) { return v; });
                 else finish_tile(tile, [&](float v) { return activate(v, a.act, a.alpha); });
                 seed();

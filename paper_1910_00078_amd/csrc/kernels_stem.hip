@@ -88,6 +88,7 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     CVX_TRACE_MARK(0);
+    warm_kernel_arguments<sizeof(ConvArgs) + sizeof(StemGeom)>();
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
@@ -480,6 +481,7 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     CVX_TRACE_MARK(0);
+    warm_kernel_arguments<sizeof(ConvArgs) + sizeof(StemGeom)>();
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int HoWo = a.Ho * a.Wo;
@@ -646,6 +648,8 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
         const bool slow_act = a.act == ACT_TANH || a.act == ACT_LOGISTIC;
         const float neg_slope = (a.act == ACT_IDENTITY || slow_act) ? 1.0f : (a.act == ACT_LEAKY_RELU ? a.alpha : 0.0f);
         const bool bn_inline = has_bn && !slow_act;
+        const bool packed_act = !has_bn && (a.act == ACT_RELU || a.act == ACT_IDENTITY);
+        const uint32_t floor2 = packed_floor(a.act == ACT_RELU);
 
         bar();                                                       // filters and the first patch are in LDS
         for (int i = 0; i < n_my; ++i) {
@@ -727,20 +731,33 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
                 const bool any = P0 < npix, whole = P0 + 8 <= npix;
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) {
+                    if (packed_act) {
+                        // bias + ReLU / identity: round, then ReLU on the packed pair, 1 instruction per value
 #pragma unroll
-                    for (int tm = 0; tm < TM; ++tm)
+                        for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4) {
-                            float v[4];
-#pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                float t = acc[tm][tn][4 * q4 + j];
-                                if (bn_inline) t = fmaf(t, ca[tn].mul, ca[tn].add);
-                                v[j] = fmaf(neg_slope, fminf(t, 0.0f), fmaxf(t, 0.0f));
+                            for (int q4 = 0; q4 < 4; ++q4) {
+                                const f32x16& t = acc[tm][tn];
+                                *(uint2*)(ow + l32 * OPITCH + (tm * 32 + 8 * q4 + 4 * half) * 2) =
+                                    make_uint2(max_packed(stem_pack2<DT>(t[4 * q4], t[4 * q4 + 1]), floor2),
+                                               max_packed(stem_pack2<DT>(t[4 * q4 + 2], t[4 * q4 + 3]), floor2));
                             }
-                            *(uint2*)(ow + l32 * OPITCH + (tm * 32 + 8 * q4 + 4 * half) * 2) =
-                                make_uint2(stem_pack2<DT>(v[0], v[1]), stem_pack2<DT>(v[2], v[3]));
-                        }
+                    } else {
+#pragma unroll
+                        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                            for (int q4 = 0; q4 < 4; ++q4) {
+                                float v[4];
+#pragma unroll
+                                for (int j = 0; j < 4; ++j) {
+                                    float t = acc[tm][tn][4 * q4 + j];
+                                    if (bn_inline) t = fmaf(t, ca[tn].mul, ca[tn].add);
+                                    v[j] = fmaf(neg_slope, fminf(t, 0.0f), fmaxf(t, 0.0f));
+                                }
+                                *(uint2*)(ow + l32 * OPITCH + (tm * 32 + 8 * q4 + 4 * half) * 2) =
+                                    make_uint2(stem_pack2<DT>(v[0], v[1]), stem_pack2<DT>(v[2], v[3]));
+                            }
+                    }
                     u32x4 o[4];
 #pragma unroll
                     for (int r4 = 0; r4 < 4; ++r4) {
