@@ -306,7 +306,9 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
                     const bool more_k = ks + 1 < NKS;
                     int issued = 0;
                     auto read_next = [&]() __attribute__((always_inline)) {
-                        if (issued < TN) fb[nb][issued] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + issued * 32) * 16);
+                        // in the order the next step's MFMAs want them: pixels 0, the filters, then the other pixels
+                        if (issued == 0) fa[nb][0] = read_a(0, ks + 1);
+                        else if (issued <= TN) fb[nb][issued - 1] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + (issued - 1) * 32) * 16);
                         else fa[nb][issued - TN] = read_a(issued - TN, ks + 1);
                         ++issued;
                     };
@@ -689,7 +691,9 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
                     const bool more_k = ks + 1 < NKS;
                     int issued = 0;
                     auto read_next = [&]() __attribute__((always_inline)) {
-                        if (issued < TN) fb[nb][issued] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + issued * 32) * 16);
+                        // in the order the next step's MFMAs want them: pixels 0, the filters, then the other pixels
+                        if (issued == 0) fa[nb][0] = read_a(0, ks + 1);
+                        else if (issued <= TN) fb[nb][issued - 1] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + (issued - 1) * 32) * 16);
                         else fa[nb][issued - TN] = read_a(issued - TN, ks + 1);
                         ++issued;
                     };
