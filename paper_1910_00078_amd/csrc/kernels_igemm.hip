@@ -22,6 +22,7 @@
 #include "cvx_device.h"
 
 #include <cstdio>
+#include <type_traits>
 #include <cstdlib>
 #include <cstring>
 
@@ -39,6 +40,8 @@ struct FastDiv {
     uint32_t m, d;
     __device__ __forceinline__ int div(int n) const { return d == 1u ? n : (int)__umulhi((uint32_t)n, m); }
 };
+
+constexpr int TRASH_BYTES = 64 * 16;
 
 struct IgemmGeom {
     int NB;          // images per pixel tile
@@ -108,9 +111,10 @@ __device__ __forceinline__ uint32_t pack_halves(uint32_t a, int ha, uint32_t b, 
 // pitch WP is a multiple of 8, moving by whole rows is still a constant byte offset (18 * WP).
 __device__ __forceinline__ int lds_slot(int s) { return s + (s >> 3); }
 
-// LDS map (bytes): two stage buffers from offset 16, each an input region (xbytes, whose last 16
-// bytes are a trash slot for loader writes that must not land in the image) followed by a filter
-// region (wbytes).  After the last stage the same memory holds the output tile for the store.
+// LDS map (bytes): two stage buffers from offset 16, each an input region (xbytes, whose last
+// TRASH_BYTES are one 16-byte trash slot per lane for loader writes that must not land in the image:
+// a slot shared by all lanes would serialise every write instruction that has several lanes on it)
+// followed by a filter region (wbytes).  After the last stage the same memory holds the output tile for the store.
 //
 // The block is split by role.  The first WM*WN waves are consumers: they own the accumulators and
 // do nothing in the main loop but read fragments from LDS and issue MFMAs.  The next NPW waves are
@@ -225,18 +229,16 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
 #pragma unroll
         for (int u = 0; u < UB; ++u) {
             const int ub = utid + u * UTHREADS;
-            b_k[u] = ub % KT;
-            b_oct[u] = ub / KT;
+            b_k[u] = ub / OCT;
+            b_oct[u] = ub % OCT;
             if (!filter_wave || ub >= g.b_units) b_oct[u] = -1;
         }
 
-        // Two register sets: the loads of two stages are in flight at once, so a stage's data has
-        // two stage times to arrive from device memory.
         struct StageRegs {
             u32x4 ra[UA][8];
             u32x4 rbv[UB][BROWS];
         };
-        StageRegs R0, R1;
+        StageRegs R0;
 
         // Global loads only; nothing here consumes a loaded value, so all of a stage's loads are in
         // flight together and are first waited on in store_stage.
@@ -306,39 +308,38 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             }
         };
 
-        load_stage(0, R0);
-        if (g.n_stages > 1) load_stage(1, R1);
-
-        // a_dst: the LDS byte offset (inside the input region) each of a unit's 8 elements goes to;
-        // elements outside the image go to the region's trash slot.
         int a_dst[UA][8];
+        auto prepare_lds = [&]() __attribute__((always_inline)) {
+            // a_dst: the LDS byte offset (inside the input region) each of a unit's 8 elements goes to;
+            // elements outside the image go to the region's trash slot.
 #pragma unroll
-        for (int u = 0; u < UA; ++u) {
+            for (int u = 0; u < UA; ++u) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) a_dst[u][e] = g.xbytes - 16;
-            if (a_oct[u] >= 0) {
-                const int rel0 = a_ui[u] * 8;
-                int row = g.by_w.div(rel0);
-                int col = rel0 - row * a.W;
-                const int region = (a_oct[u] * g.NB + a_img[u]) * g.PSLOTS;
+                for (int e = 0; e < 8; ++e) a_dst[u][e] = g.xbytes - TRASH_BYTES + lane * 16;
+                if (a_oct[u] >= 0) {
+                    const int rel0 = a_ui[u] * 8;
+                    int row = g.by_w.div(rel0);
+                    int col = rel0 - row * a.W;
+                    const int region = (a_oct[u] * g.NB + a_img[u]) * g.PSLOTS;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int eabs = e_lo + rel0 + e;
-                    if (a_img[u] < nimg && eabs >= 0 && eabs < HW && row < g.PH)
-                        a_dst[u][e] = (region + lds_slot(row * g.WP + col + a.pad_w)) * 16;
-                    if (++col == a.W) { col = 0; ++row; }
+                    for (int e = 0; e < 8; ++e) {
+                        const int eabs = e_lo + rel0 + e;
+                        if (a_img[u] < nimg && eabs >= 0 && eabs < HW && row < g.PH)
+                            a_dst[u][e] = (region + lds_slot(row * g.WP + col + a.pad_w)) * 16;
+                        if (++col == a.W) { col = 0; ++row; }
+                    }
                 }
             }
-        }
-        {
-            // zero both input regions: pad columns and rows outside the image are never written
-            // afterwards, so they stay zero for every stage
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            for (int i = ptid * 16; i < g.xbytes; i += PTHREADS * 16) {
-                *(u32x4*)(smem + BUF0 + i) = z;
-                *(u32x4*)(smem + BUF0 + stage_bytes + i) = z;
+            {
+                // zero both input regions: pad columns and rows outside the image are never written
+                // afterwards, so they stay zero for every stage
+                const u32x4 z = {0u, 0u, 0u, 0u};
+                for (int i = ptid * 16; i < g.xbytes; i += PTHREADS * 16) {
+                    *(u32x4*)(smem + BUF0 + i) = z;
+                    *(u32x4*)(smem + BUF0 + stage_bytes + i) = z;
+                }
             }
-        }
+        };
 
         auto store_stage = [&](int st, int buf, const StageRegs& R) {
             auto& ra = R.ra;
@@ -392,29 +393,167 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             }
         };
 
-        __syncthreads();                               // (A) zero fill complete
-        store_stage(0, 0, R0);
-        if (g.n_stages > 2) load_stage(2, R0);
-        __syncthreads();                               // (B) stage 0 is in LDS
-        CVX_TRACE_MARK_T(2, NCW * 64);
-        // Each pass hands the consumers one stage: while they multiply stage st, stage st+1 is
-        // transposed into the other LDS buffer (this waits for its loads) and the loads of stage
-        // st+3 take over the registers just freed.  Unrolled by two so the register sets alternate
-        // at compile time.
-        for (int st = 0; st < g.n_stages; st += 2) {
-            if (st + 1 < g.n_stages) {
-                store_stage(st + 1, 1, R1);
-                if (st + 3 < g.n_stages) load_stage(st + 3, R1);
+        // ---- the common case, with nothing conditional in it ---------------------------------------
+        // The general loop above takes a different number of loads per stage depending on run-time
+        // conditions (ragged channels or filters, offsets outside the tensor, lanes without a unit), so
+        // the compiler cannot know how many loads are in flight behind the ones a stage needs and
+        // waits for all of them: the second register set then buys nothing.  When every unit of every
+        // stage of this wave is a plain in-bounds load, the loop below issues a fixed number of loads
+        // per stage (lanes without a unit fetch a valid address and write nothing), and the waits become
+        // "all but the newest stage" (c5b 50.0 -> 45.4 us).  Not for kernels with several units per
+        // thread (no registers for two sets of them), and not for the twelve-wave kernels: their eight
+        // producer waves already keep the memory pipeline full, and two stages of loads in flight per
+        // wave measured slower (c5a 45.2 us against 43.9).
+        constexpr bool FASTABLE = TAPS > 0 && UA == 1 && UB == 1 && !SPLIT;
+        bool fast_lane = FASTABLE && (g.n_stages & 1) == 0 && g.cg % CC == 0 && k0 + KT <= k_end;
+        long long w_goff[UB];
+        int w_dst[UB];
+        {
+            const long long span = (long long)(g.n_stages - 1) * CC * HW + 7LL * HW + 8;
+#pragma unroll
+            for (int u = 0; u < UA; ++u) {
+                if (a_oct[u] < 0) a_goff[u] = ((long long)n0 * a.C + c_first) * HW + e_lo;
+                if (input_wave) fast_lane = fast_lane && a_goff[u] >= 0 && a_goff[u] + span <= x_total;
             }
-            if (st < 6) CVX_TRACE_MARK_T(4 + 2 * st, NCW * 64);
-            __syncthreads();                           // stage st consumed, stage st+1 in LDS
-            if (st + 1 < g.n_stages) {
-                if (st + 2 < g.n_stages) {
-                    store_stage(st + 2, 0, R0);
-                    if (st + 4 < g.n_stages) load_stage(st + 4, R0);
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int ub = utid + u * UTHREADS;
+                const bool live = ub < g.b_units;
+                const int k = live ? ub / OCT : 0, oct = live ? ub % OCT : 0;
+                w_goff[u] = ((long long)(k0 + k) * g.cg + oct * 8) * (TAPS > 0 ? TAPS : 1);
+                w_dst[u] = live ? (oct * KT + k) * 16 : -1;
+            }
+        }
+        const bool fast_wave = __builtin_amdgcn_ballot_w64(!fast_lane) == 0ull;
+
+        auto run_fast = [&]() __attribute__((always_inline)) {
+            constexpr bool DO_X = true, DO_W = true;
+            u32x4 xa[2][UA][8];
+            u32x4 wb[2][UB][BROWS];
+            const int last = g.n_stages - 1;
+            auto load = [&](int st, auto set_c) __attribute__((always_inline)) {
+                constexpr int SET = decltype(set_c)::value;
+                // past the last stage the same number of loads is issued, all lanes at the start of the
+                // tensor (one cache line; the values are never used)
+                const bool real = st <= last;
+                const int cbase = st * CC;
+                if constexpr (DO_X) {
+#pragma unroll
+                    for (int u = 0; u < UA; ++u) {
+                        const uint16_t* p = real ? xg + a_goff[u] + (long long)cbase * HW : xg;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) xa[SET][u][j] = *(const u32x4_a2*)(p + (long long)j * HW);
+                    }
                 }
-                if (st + 1 < 6) CVX_TRACE_MARK_T(4 + 2 * (st + 1), NCW * 64);
+                if constexpr (DO_W) {
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) {
+                        const uint16_t* p = real ? wg + w_goff[u] + (long long)cbase * TAPS : wg;
+#pragma unroll
+                        for (int i = 0; i < BROWS; ++i) wb[SET][u][i] = *(const u32x4_a2*)(p + i * 8);
+                    }
+                }
+            };
+            // One half-iteration: transpose register set SET (stage s) into temporaries, refill the set
+            // with the loads of stage s+2 right away (the transposed copy is what gets written), then
+            // write the temporaries into LDS buffer `buf`.  Lanes without a unit skip only the writes.
+            auto step = [&](int buf, auto set_c, int st_next, auto refill_c) __attribute__((always_inline)) {
+                constexpr int SET = decltype(set_c)::value;
+                constexpr bool REFILL = decltype(refill_c)::value;
+                unsigned char* xs = smem + BUF0 + buf * stage_bytes;
+                const bool real = st_next <= last;
+                const int cbase = st_next * CC;
+                if constexpr (DO_X) {
+#pragma unroll
+                    for (int u = 0; u < UA; ++u) {
+                        u32x4 o[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+#pragma unroll
+                            for (int m = 0; m < 4; ++m)
+                                o[e][m] = pack_halves(xa[SET][u][2 * m + 1][e >> 1], e & 1, xa[SET][u][2 * m][e >> 1], e & 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (REFILL) {
+                            const uint16_t* p = real ? xg + a_goff[u] + (long long)cbase * HW : xg;
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) xa[SET][u][j] = *(const u32x4_a2*)(p + (long long)j * HW);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (a_oct[u] >= 0) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) *(u32x4*)(xs + a_dst[u][e]) = o[e];
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+                if constexpr (DO_W) {
+                    unsigned char* ws = xs + g.xbytes;
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) {
+                        u32x4 o[TAPS > 0 ? TAPS : 1];
+#pragma unroll
+                        for (int tap = 0; tap < TAPS; ++tap)
+#pragma unroll
+                            for (int m = 0; m < 4; ++m) {
+                                const int t0 = (2 * m) * TAPS + tap, t1 = (2 * m + 1) * TAPS + tap;
+                                o[tap][m] = pack_halves(wb[SET][u][t1 >> 3][(t1 >> 1) & 3], t1 & 1,
+                                                        wb[SET][u][t0 >> 3][(t0 >> 1) & 3], t0 & 1);
+                            }
+                        __builtin_amdgcn_sched_barrier(0);
+                        if constexpr (REFILL) {
+                            const uint16_t* p = real ? wg + w_goff[u] + (long long)cbase * TAPS : wg;
+#pragma unroll
+                            for (int i = 0; i < BROWS; ++i) wb[SET][u][i] = *(const u32x4_a2*)(p + i * 8);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (w_dst[u] >= 0) {
+#pragma unroll
+                            for (int tap = 0; tap < TAPS; ++tap) *(u32x4*)(ws + tap * OCT * KT * 16 + w_dst[u]) = o[tap];
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            };
+            const std::integral_constant<int, 0> s0;
+            const std::integral_constant<int, 1> s1;
+            load(0, s0);
+            load(1, s1);
+            prepare_lds();
+            __syncthreads();                           // (A) zero fill complete
+            const std::true_type refill;
+            step(0, s0, 2, refill);                    // stage 0 into LDS, stage 2 into its registers
+            __syncthreads();                           // (B) stage 0 is in LDS
+            for (int st = 0; st + 2 < g.n_stages; st += 2) {
+                step(1, s1, st + 3, refill);           // stage st+1
+                __syncthreads();                       // stage st consumed, stage st+1 in LDS
+                step(0, s0, st + 4, refill);           // stage st+2
                 __syncthreads();                       // stage st+1 consumed, stage st+2 in LDS
+            }
+            step(1, s1, 0, std::false_type());         // the last stage; nothing follows it
+            __syncthreads();
+            __syncthreads();                           // the consumers' barrier after the last stage
+        };
+
+        if (FASTABLE && fast_wave) {
+            run_fast();
+        } else {
+            // general loop (ragged tiles, tensor edges, odd stage counts, filter sizes without a compiled
+            // transpose): one register set; the loads of stage st+2 are issued once stage st+1 has been
+            // transposed out of it
+            load_stage(0, R0);
+            prepare_lds();
+            __syncthreads();                               // (A) zero fill complete
+            store_stage(0, 0, R0);
+            if (g.n_stages > 1) load_stage(1, R0);
+            __syncthreads();                               // (B) stage 0 is in LDS
+            CVX_TRACE_MARK_T(2, NCW * 64);
+            for (int st = 0; st < g.n_stages; ++st) {
+                if (st + 1 < g.n_stages) {
+                    store_stage(st + 1, (st + 1) & 1, R0);
+                    if (st + 2 < g.n_stages) load_stage(st + 2, R0);
+                }
+                if (st < 6) CVX_TRACE_MARK_T(4 + 2 * st, NCW * 64);
+                __syncthreads();                           // stage st consumed, stage st+1 in LDS
             }
         }
     } else {
@@ -786,7 +925,7 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     g.a_units = (int)a_units;
     g.b_units = v.TAPS > 0 ? KT * OCT : 0;
     if (g.b_units > v.UB * threads) return false;
-    const long long xb = (long long)OCT * g.NB * g.PSLOTS * 16 + 16, wb = (long long)taps * OCT * KT * 16;
+    const long long xb = (long long)OCT * g.NB * g.PSLOTS * 16 + TRASH_BYTES, wb = (long long)taps * OCT * KT * 16;
     if (16 + 2 * (xb + wb) > LDS_LIMIT) return false;
     g.xbytes = (int)xb;
     g.wbytes = (int)wb;
