@@ -17,8 +17,8 @@
 //   Padding          rows outside the image are zero-filled by the loader; columns outside the
 //                    image are redirected at read time to a 16-byte slot of zeros.
 //   Filters in LDS   [tap][octet][filter] x 16 bytes, transposed in registers the same way.
-//   Pipeline         two LDS stage buffers; global loads of stage s+1 are in flight while stage s
-//                    is multiplied.
+//   Pipeline         two LDS stage buffers; the global loads of the next stage (of the next two, in
+//                    the producers' common-case loop) are in flight while stage s is multiplied.
 #include "cvx_device.h"
 
 #include <cstdio>
@@ -112,14 +112,14 @@ __device__ __forceinline__ uint32_t pack_halves(uint32_t a, int ha, uint32_t b, 
 __device__ __forceinline__ int lds_slot(int s) { return s + (s >> 3); }
 
 // LDS map (bytes): two stage buffers from offset 16, each an input region (xbytes, whose last
-// TRASH_BYTES are one 16-byte trash slot per lane for loader writes that must not land in the image:
-// a slot shared by all lanes would serialise every write instruction that has several lanes on it)
-// followed by a filter region (wbytes).  After the last stage the same memory holds the output tile for the store.
+// TRASH_BYTES are one 16-byte trash slot per lane for loader writes that must not land in the image,
+// so that no two lanes of a write instruction share an address) followed by a filter region
+// (wbytes).  After the last stage the same memory holds the output tile for the store.
 //
 // The block is split by role.  The first WM*WN waves are consumers: they own the accumulators and
 // do nothing in the main loop but read fragments from LDS and issue MFMAs.  The next NPW waves are
-// producers: they fetch stage s+2 from device memory, and transpose and write stage s+1 into LDS,
-// while the consumers multiply stage s.  One consumer and one producer wave share each SIMD, so the
+// producers: they transpose and write stage s+1 into LDS, and fetch a later stage from device
+// memory, while the consumers multiply stage s.  One consumer and one producer wave share each SIMD, so the
 // producers' vector-ALU and memory work runs in the shadow of the matrix pipe.  One s_barrier per
 // stage hands a finished buffer from producers to consumers and a drained one back.
 // 8: four producer waves for the input and four for the filters; 4: four that do both (kernels whose
@@ -253,13 +253,8 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                     const long long off0 = a_goff[u] + (long long)cbase * HW;
                     const bool fast = off0 >= 0 && off0 + 7LL * HW + 8 <= x_total && c0 + 8 <= g.cg;
                     if (fast) {
-#ifdef CVX_EXP_NO_XLOAD
-#pragma unroll
-                        for (int j = 0; j < 8; ++j) ra[u][j] = u32x4{(uint32_t)j, 0u, 0u, 0u};
-#else
 #pragma unroll
                         for (int j = 0; j < 8; ++j) ra[u][j] = *(const u32x4_a2*)(xg + off0 + (long long)j * HW);
-#endif
                     } else {
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
@@ -281,10 +276,6 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                         if (full) {
 #pragma unroll
                             for (int i = 0; i < BROWS; ++i) {
-#ifdef CVX_EXP_NO_WLOAD
-                                rbv[u][i] = u32x4{(uint32_t)i, 0u, 0u, 0u};
-                                continue;
-#endif
                                 if (i * 8 + 8 <= 8 * TAPS) rbv[u][i] = *(const u32x4_a2*)(wg + off0 + i * 8);
                                 else rbv[u][i] = load8(wg, off0 + i * 8, w_total);
                             }
@@ -621,9 +612,6 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
         // and the waits the compiler inserts are partial.
         auto compute_stage = [&](int buf) {
             if (!wave_on) return;
-#ifdef CVX_EXP_NO_MFMA
-            return;
-#endif
             const unsigned char* xs = smem + BUF0 + buf * stage_bytes;
             const unsigned char* ws = xs + g.xbytes + b_lane;
             if constexpr (TAPS == 9 || TAPS == 1) {
