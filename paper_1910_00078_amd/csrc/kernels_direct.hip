@@ -7,7 +7,10 @@
 
 namespace cvx {
 
-template <int DT>
+// CS = 1: one thread per output.  CS = 8: eight neighbouring lanes share an output, each taking every
+// eighth channel, and add their partial sums with three lane exchanges: small problems are a chain of
+// dependent loads per thread, and this cuts the chain by eight.
+template <int DT, int CS>
 __global__ void __launch_bounds__(256) direct_conv_kernel(ConvArgs a)
 {
     warm_kernel_arguments<sizeof(ConvArgs)>();
@@ -15,8 +18,9 @@ __global__ void __launch_bounds__(256) direct_conv_kernel(ConvArgs a)
     const int cg = a.C / a.groups;
     const int kg = a.K / a.groups;
     const bool has_bn = a.bn_scale != nullptr;
-    for (long long o = (long long)blockIdx.x * blockDim.x + threadIdx.x; o < total;
-         o += (long long)gridDim.x * blockDim.x) {
+    const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int part = (int)(tid % CS);
+    for (long long o = tid / CS; o < total; o += (long long)gridDim.x * blockDim.x / CS) {
         const int q = (int)(o % a.Wo);
         long long t = o / a.Wo;
         const int p = (int)(t % a.Ho);
@@ -27,7 +31,7 @@ __global__ void __launch_bounds__(256) direct_conv_kernel(ConvArgs a)
         const int h0 = p * a.stride_h - a.pad_h;
         const int w0 = q * a.stride_w - a.pad_w;
         float acc = 0.0f;
-        for (int c = 0; c < cg; ++c) {
+        for (int c = part; c < cg; c += CS) {
             const size_t xbase = ((size_t)n * a.C + (c0 + c)) * a.H * a.W;
             const size_t wbase = ((size_t)k * cg + c) * a.R * a.S;
             for (int r = 0; r < a.R; ++r) {
@@ -41,6 +45,12 @@ __global__ void __launch_bounds__(256) direct_conv_kernel(ConvArgs a)
                 }
             }
         }
+        if constexpr (CS > 1) {
+            // the CS lanes of an output are neighbours in one wave and reach this point together
+#pragma unroll
+            for (int d = 1; d < CS; d <<= 1) acc += __shfl_xor(acc, d);
+            if (part != 0) continue;
+        }
         const ChannelAffine ca = channel_affine<DT>(a, k);
         Elem<DT>::store(a.y, (size_t)o, finish(acc, ca, has_bn, a.act, a.alpha));
     }
@@ -49,15 +59,22 @@ __global__ void __launch_bounds__(256) direct_conv_kernel(ConvArgs a)
 hipError_t launch_direct(const ConvArgs& a, hipStream_t s)
 {
     const long long total = (long long)a.N * a.K * a.Ho * a.Wo;
-    long long blocks = (total + 255) / 256;
+    const bool split = total <= 32768 && a.C / a.groups >= 8;      // latency-bound sizes
+    long long blocks = (total * (split ? 8 : 1) + 255) / 256;
     if (blocks > (1 << 20)) blocks = 1 << 20;           // grid-stride loop covers the rest
     const dim3 grid((unsigned)blocks), block(256);
+#define CVX_LAUNCH_DIRECT(DT)                                                                   \
+    do {                                                                                        \
+        if (split) hipLaunchKernelGGL((direct_conv_kernel<DT, 8>), grid, block, 0, s, a);       \
+        else hipLaunchKernelGGL((direct_conv_kernel<DT, 1>), grid, block, 0, s, a);             \
+    } while (0)
     switch (a.dtype) {
-    case DT_F32:  hipLaunchKernelGGL(direct_conv_kernel<DT_F32>, grid, block, 0, s, a); break;
-    case DT_F16:  hipLaunchKernelGGL(direct_conv_kernel<DT_F16>, grid, block, 0, s, a); break;
-    case DT_BF16: hipLaunchKernelGGL(direct_conv_kernel<DT_BF16>, grid, block, 0, s, a); break;
+    case DT_F32:  CVX_LAUNCH_DIRECT(DT_F32); break;
+    case DT_F16:  CVX_LAUNCH_DIRECT(DT_F16); break;
+    case DT_BF16: CVX_LAUNCH_DIRECT(DT_BF16); break;
     default: return hipErrorInvalidValue;
     }
+#undef CVX_LAUNCH_DIRECT
     return hipGetLastError();
 }
 
