@@ -790,6 +790,22 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             const bool whole = rem + 8 <= ppi;     // all 8 pixels valid and inside one image
             uint16_t* __restrict__ yg = (uint16_t*)a.y;
             const size_t obase = ((size_t)(n0 + img) * a.K + k0) * HoWo + (size_t)p0 * a.Wo + rem;
+            // A chunk that straddles an image boundary or the end of the tile is stored element by
+            // element; where each element goes (relative to the chunk's first) is the same for every
+            // filter row, so it is worked out once, by stepping, not by dividing: -1 = past the tile.
+            int eoff[8];
+            if (!whole) {
+                int r = rem, jump = 0;                 // jump: offset of the current image relative to the first
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (r == ppi) {                    // next image of the tile: K * HoWo further, back at its first pixel
+                        r = 0;
+                        jump += a.K * HoWo - ppi;
+                    }
+                    eoff[e] = f0 + e < npix ? e + jump : -1;
+                    ++r;
+                }
+            }
             constexpr int GRP = NPASS >= 4 ? 4 : NPASS;
             for (int p = 0; p < NPASS; p += GRP) {
                 u32x4 v[GRP];
@@ -809,18 +825,8 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                         } else {
                             // chunk straddles an image boundary or the end of the tile: element-wise
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                const int f = f0 + e;
-                                if (f < npix) {
-                                    int im2 = 0, rm2 = f;
-                                    if (g.NB > 1) {
-                                        im2 = f / ppi;
-                                        rm2 = f - im2 * ppi;
-                                    }
-                                    yg[((size_t)(n0 + im2) * a.K + k0 + kl) * HoWo + (size_t)p0 * a.Wo + rm2] =
-                                        (uint16_t)(v[j][e >> 1] >> ((e & 1) * 16));
-                                }
-                            }
+                            for (int e = 0; e < 8; ++e)
+                                if (eoff[e] >= 0) dst[eoff[e]] = (uint16_t)(v[j][e >> 1] >> ((e & 1) * 16));
                         }
                     }
                 }
