@@ -1,6 +1,7 @@
 """GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on the same
 seeded inputs, element by element.  Tolerances: fp32 relative L2 <= 1e-5; fp16/bf16 every element
 within 1e-2*|ref| + 1e-3*rms(ref)."""
+import os
 import sys
 
 import numpy as np
@@ -115,6 +116,41 @@ def test_reduced_shapes(w):
 @pytest.mark.parametrize("w", SMALL[::3], ids=lambda w: w.name)
 def test_reduced_shapes_generic_kernel(w):
     check_case(w, policy=1)
+
+
+PINNED = [
+    # name, variant, workload: the eight-wave implicit-GEMM kernels are chosen on their own only for the
+    # full-size layers; pinned, their two producer loops (the fixed-load-count one for blocks in the
+    # interior of the tensor, the general one at its edges and for ragged shapes) and the skipping of
+    # empty pixel tiles are exercised on small tensors too
+    ("p512_c64_k64", "igemm_512x64_c16_3x3", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=40, W=40)),
+    ("p512_no_pad", "igemm_512x64_c16_3x3", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=40, W=40, pad=(0, 0))),
+    ("p512_odd_stages", "igemm_512x64_c16_3x3", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=28, W=28, C=48)),
+    ("p512_ragged_filters", "igemm_512x64_c16_3x3", wl.small_variant(wl.WORKLOADS["c2"], N=5, H=28, W=28, K=48)),
+    ("p512_whole_images", "igemm_512x64_c16_3x3", wl.small_variant(wl.WORKLOADS["c5a"], N=16, C=64, K=64)),
+    ("p256x128_stride2", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=64, K=128)),
+    ("p256x128_ragged_filters", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=32, K=200)),
+    ("p256x128_whole_images", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5a"], N=9, C=128, K=128)),
+]
+
+
+@pytest.mark.parametrize("case", PINNED, ids=lambda c: c[0])
+def test_pinned_eight_wave_variants(case):
+    _, variant, w = case
+    PT = 512 if "512x64" in variant else 256
+    Ho = (w.H + 2 * w.pad[0] - w.dil[0] * (w.R - 1) - 1) // w.stride[0] + 1
+    Wo = (w.W + 2 * w.pad[1] - w.dil[1] * (w.S - 1) - 1) // w.stride[1] + 1
+    nb, th = (min(w.N, PT // (Ho * Wo)), Ho) if Ho * Wo <= PT else (1, PT // Wo)
+    say("case %s pinned to %s NB=%d TH=%d: N=%d C=%d H=%d W=%d K=%d pad=%s stride=%s" % (case[0], variant, nb, th, w.N, w.C, w.H, w.W, w.K, w.pad, w.stride))
+    x, wt, b = wl.make_inputs(w)
+    os.environ["CVX_IGEMM_FORCE"] = "%s,%d,%d" % (variant, nb, th)
+    try:
+        got, name = run_gpu(w, x, wt, b)
+    finally:
+        os.environ["CVX_IGEMM_FORCE"] = ""
+    assert name == variant
+    ok, msg = tolerance_ok(got, run_oracle(w, x, wt, b), w.dtype)
+    assert ok, msg
 
 
 def test_kernel_families_serve_the_shapes_they_were_built_for():
