@@ -806,6 +806,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                     ++r;
                 }
             }
+            const bool tail4 = !whole && f0 + 4 == npix && rem + 4 <= ppi;   // four live pixels, all in one image
             constexpr int GRP = NPASS >= 4 ? 4 : NPASS;
             for (int p = 0; p < NPASS; p += GRP) {
                 u32x4 v[GRP];
@@ -824,9 +825,14 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                             __builtin_nontemporal_store(v[j], (u32x4_a2*)dst);
                         } else {
                             // chunk straddles an image boundary or the end of the tile: element-wise
+                            if (tail4 && (((uintptr_t)dst) & 7) == 0) {
+                                // the tile ends after this chunk's first four pixels: one 8-byte store
+                                *(uint2*)dst = make_uint2(v[j][0], v[j][1]);
+                            } else {
 #pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (eoff[e] >= 0) dst[eoff[e]] = (uint16_t)(v[j][e >> 1] >> ((e & 1) * 16));
+                                for (int e = 0; e < 8; ++e)
+                                    if (eoff[e] >= 0) dst[eoff[e]] = (uint16_t)(v[j][e >> 1] >> ((e & 1) * 16));
+                            }
                         }
                     }
                 }
