@@ -21,15 +21,84 @@ def _cases():
         return json.load(f)["cases"]
 
 
+def _run_case(conv_fwd, case):
+    bn = case.get("bn")
+    if bn is not None:
+        bn = tuple(np.array(bn[k], float) for k in ("scale", "shift", "mean", "var"))
+    return conv_fwd(np.array(case["x"], float), np.array(case["w"], float),
+                    None if case["bias"] is None else np.array(case["bias"], float),
+                    pad=tuple(case["pad"]), stride=tuple(case["stride"]), dil=tuple(case["dil"]),
+                    act=ACTS[case["act"]], alpha=case.get("alpha", 0.0), bn=bn, eps=case.get("eps", 0.0))
+
+
+def _case_ok(y, case):
+    """Exact equality unless the case carries a tolerance (inputs such as ln 2 that are themselves
+    rounded); the expected values are the file's, worked by hand."""
+    want = np.array(case["y"], float)
+    if y.shape != want.shape:
+        return False
+    if "tol" in case:
+        return bool(np.all(np.abs(y - want) <= case["tol"]))
+    return bool(np.array_equal(y, want))
+
+
 @pytest.mark.parametrize("case", _cases(), ids=lambda c: c["name"])
 def test_hand_worked_examples(oracle, case):
-    y = oracle.conv_fwd(np.array(case["x"], float), np.array(case["w"], float),
-                        None if case["bias"] is None else np.array(case["bias"], float),
-                        pad=tuple(case["pad"]), stride=tuple(case["stride"]), dil=tuple(case["dil"]),
-                        act=ACTS[case["act"]])
-    want = np.array(case["y"], float)
-    assert y.shape == want.shape
-    assert np.array_equal(y, want), (case["name"], y)
+    y = _run_case(oracle.conv_fwd, case)
+    assert _case_ok(y, case), (case["name"], y)
+
+
+# Mistakes planted in a COPY of the oracle's source (compiled on the CPU into a temporary library):
+# each must be caught by at least one hand-worked case, which shows that the cases pin the line
+# they are meant to pin.  (original text, replacement, cases expected to notice)
+PLANTED = [
+    ("sqrt(var + eps)", "(var + eps)", {"G_bias_batchnorm", "H_batchnorm_per_channel"}),
+    ("sqrt(var + eps)", "(sqrt(var) + eps)", {"G_bias_batchnorm", "H_batchnorm_per_channel"}),
+    ("(v - mean)", "(v + mean)", {"G_bias_batchnorm", "H_batchnorm_per_channel"}),
+    ("gamma = bn[k], beta = bn[K + k]", "gamma = bn[K + k], beta = bn[k]", {"G_bias_batchnorm"}),
+    ("mean = bn[2 * K + k], var = bn[3 * K + k]", "mean = bn[3 * K + k], var = bn[2 * K + k]", {"G_bias_batchnorm"}),
+    ("mean = bn[2 * K + k]", "mean = bn[2 * K]", {"H_batchnorm_per_channel"}),
+    ("double v = acc + (b ? b[k] : 0.0);", "double v = acc;", {"G_bias_batchnorm", "D_bias_relu"}),
+    ("v = gamma * (v - mean) / sqrt(var + eps) + beta;\n    }\n    return apply_act(v, act, alpha);",
+     "v = gamma * (apply_act(v, act, alpha) - mean) / sqrt(var + eps) + beta; return v;\n    }\n    return apply_act(v, act, alpha);",
+     {"G2_bias_batchnorm_relu"}),
+    ("case ACT_LEAKY_RELU: return v > 0.0 ? v : alpha * v;", "case ACT_LEAKY_RELU: return v > 0.0 ? v : 0.0;", {"I_leaky_relu"}),
+    ("case ACT_LEAKY_RELU: return v > 0.0 ? v : alpha * v;", "case ACT_LEAKY_RELU: return v > 0.0 ? alpha * v : v;", {"I_leaky_relu"}),
+    ("return tanh(v);", "return 1.0 / (1.0 + exp(-v));", {"J_tanh_closed_forms"}),
+    ("return tanh(v);", "return tanh(0.5 * v);", {"J_tanh_closed_forms"}),
+    ("return 1.0 / (1.0 + exp(-v));", "return 1.0 / (1.0 + exp(v));", {"K_logistic_closed_forms"}),
+    ("return 1.0 / (1.0 + exp(-v));", "return tanh(v);", {"K_logistic_closed_forms"}),
+    ("p * stride_h - pad_h + r * dil_h", "p * stride_h - pad_h + (R - 1 - r) * dil_h", {"A_valid"}),
+    ("q * stride_w - pad_w + s * dil_w", "q * stride_w + pad_w + s * dil_w", {"B_pad1"}),
+]
+
+
+@pytest.mark.parametrize("old,new,catchers", PLANTED, ids=[str(i) for i in range(len(PLANTED))])
+def test_planted_mistakes_are_caught(oracle, tmp_path, old, new, catchers):
+    import ctypes
+    import subprocess
+    from oracle import conv_oracle as mod
+    src = open(os.path.join(os.path.dirname(mod.__file__), "conv_oracle.c")).read()
+    assert src.count(old) == 1, "the oracle line this mistake is planted in has changed: %r" % old
+    bad_c, bad_so = tmp_path / "bad.c", tmp_path / "libbad.so"
+    bad_c.write_text(src.replace(old, new))
+    subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared", "-o", str(bad_so), str(bad_c), "-lm"])
+    good_lib = mod._lib
+    try:
+        mod._lib = None
+        real_cdll = ctypes.CDLL
+        # load the perturbed library through the module's own marshalling code
+        mod.ctypes.CDLL = lambda path, *a, **k: real_cdll(str(bad_so), *a, **k)
+        try:
+            mod._load()
+        finally:
+            mod.ctypes.CDLL = real_cdll
+        failed = {c["name"] for c in _cases() if not _case_ok(_run_case(mod.conv_fwd, c), c)}
+    finally:
+        mod._lib = good_lib
+    assert catchers <= failed, "planted %r -> %r: cases that noticed: %s" % (old, new, sorted(failed))
+    for c in _cases():                                   # and the real oracle still passes them all
+        assert _case_ok(_run_case(oracle.conv_fwd, c), c)
 
 
 def test_cross_correlation_not_flipped(oracle):
