@@ -62,7 +62,7 @@ def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = Fa
     set_bytes = w.elem_bytes * (w.N * w.C * w.H * w.W + w.N * w.K * w.Ho * w.Wo)
     nsets = min(64, max(2, -(-ROTATE_BYTES // set_bytes)))
     xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
-    ys = [torch.empty(plan.y_shape, dtype=x0.dtype, device="cuda") for _ in range(nsets)]
+    ys = [torch.full(plan.y_shape, float("nan"), dtype=x0.dtype, device="cuda") for _ in range(nsets)]
 
     def step(i):
         j = i % nsets

@@ -56,8 +56,11 @@ def run_gpu(w: wl.ConvWorkload, x, wt, b, *, act=cvx.CVX_ACT_RELU, alpha=0.0, po
     if use_bias:
         db = torch.from_numpy(wl.to_f64(b, w.dtype).astype(np.float32)).cuda() if bias_f32 else to_device(b, w.dtype)
     dbn = None if bn is None else tuple(torch.from_numpy(np.asarray(t, np.float32)).cuda() for t in bn)
-    y = cvx.conv_fwd_fused(dx, dw, db, pad=w.pad, stride=w.stride, dil=w.dil, groups=w.groups, act=act,
-                           alpha=alpha, bn=dbn, eps=eps, policy=policy)
+    # every output element starts as NaN: one the kernel never writes fails the comparison instead of
+    # showing whatever the allocator left there (possibly an earlier case's correct result)
+    y = torch.full((w.N, w.K, w.Ho, w.Wo), float("nan"), dtype=dx.dtype, device="cuda")
+    cvx.conv_fwd_fused(dx, dw, db, pad=w.pad, stride=w.stride, dil=w.dil, groups=w.groups, act=act,
+                       alpha=alpha, bn=dbn, eps=eps, policy=policy, out=y)
     torch.cuda.synchronize()
     plan = cvx.ConvPlan(DT_CODE[w.dtype], (w.N, w.C, w.H, w.W), (w.K, w.C // w.groups, w.R, w.S), w.pad, w.stride,
                         w.dil, w.groups)

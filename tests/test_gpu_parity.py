@@ -210,7 +210,7 @@ def test_plain_conv_fwd_and_unfused_operators_agree_with_fused():
     x, wt, b = wl.make_inputs(w)
     dx, dw, db = to_device(x, w.dtype), to_device(wt, w.dtype), to_device(b, w.dtype)
     plan = cvx.ConvPlan(DT_CODE[w.dtype], tuple(dx.shape), tuple(dw.shape), w.pad, w.stride, w.dil)
-    y = torch.empty(plan.y_shape, dtype=dx.dtype, device="cuda")
+    y = torch.full(plan.y_shape, float("nan"), dtype=dx.dtype, device="cuda")
     plan.run_plain(dx.data_ptr(), dw.data_ptr(), y.data_ptr())
     torch.cuda.synchronize()
     ref_plain = run_oracle(w, x, wt, b, act=0, use_bias=False)
@@ -287,7 +287,7 @@ def test_non_default_stream_and_reused_plan():
     with torch.cuda.stream(s):
         plan = cvx.ConvPlan(DT_CODE[w.dtype], tuple(dx.shape), tuple(dw.shape), w.pad, w.stride, w.dil,
                             stream=s.cuda_stream)
-        y = torch.empty(plan.y_shape, dtype=dx.dtype, device="cuda")
+        y = torch.full(plan.y_shape, float("nan"), dtype=dx.dtype, device="cuda")
         for _ in range(3):
             plan.run(dx.data_ptr(), dw.data_ptr(), db.data_ptr(), y.data_ptr())
         s.synchronize()
