@@ -129,6 +129,15 @@ __host__ __device__ constexpr int igemm_producer_waves(int TM, int TN, int TAPS,
     return (TM * TN <= 4 && !(TAPS == 9 && (UA > 1 || UB > 1))) ? 8 : 4;
 }
 
+// Filter region of a stage: [tap][octet][filter] x 16 bytes.  The loader's lanes are dealt octet-fastest, so
+// the 8 lanes of one 128-byte beat of a write differ in their octet; with octets exactly KT * 16 bytes apart
+// (a multiple of 128) they would all land on the same banks.  A skew of 128 / OCT bytes per octet spreads
+// them; the consumers' fragment reads (32 consecutive filters of one octet) stay contiguous.
+__host__ __device__ constexpr int igemm_filter_octet_pitch(int KT, int OCT)
+{
+    return KT * 16 + (OCT > 1 ? (128 / OCT < 16 ? 16 : 128 / OCT) : 0);
+}
+
 template <int DT, int WM, int WN, int TM, int TN, int CC, int TAPS, int UA, int UB>
 __global__ void __launch_bounds__((WM * WN + igemm_producer_waves(TM, TN, TAPS, UA, UB)) * 64)
 igemm_kernel(ConvArgs a, IgemmGeom g)
@@ -148,6 +157,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     constexpr int OCT = CC / 8;
     constexpr int KSTEPS = CC / 16;
     constexpr int PTP = PT + 8;            // pixel pitch of the staged output tile
+    constexpr int WOP = igemm_filter_octet_pitch(KT, OCT);   // bytes between the octets of one tap in the filter region
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int BUF0 = 16;
 
@@ -364,7 +374,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                                 o[m] = pack_halves(rbv[u][t1 >> 3][(t1 >> 1) & 3], t1 & 1,
                                                    rbv[u][t0 >> 3][(t0 >> 1) & 3], t0 & 1);
                             }
-                            *(u32x4*)(ws + ((tap * OCT + b_oct[u]) * KT + b_k[u]) * 16) = o;
+                            *(u32x4*)(ws + (tap * OCT + b_oct[u]) * WOP + b_k[u] * 16) = o;
                         }
                     }
                 }
@@ -378,7 +388,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                     const long long off0 = ((long long)k * g.cg + c) * taps;
                     for (int t = 0; t < taps; ++t) {
                         const uint16_t v = ok ? wg[off0 + t] : (uint16_t)0;
-                        *(uint16_t*)(ws + ((t * OCT + (cl >> 3)) * KT + kl) * 16 + (cl & 7) * 2) = v;
+                        *(uint16_t*)(ws + (t * OCT + (cl >> 3)) * WOP + kl * 16 + (cl & 7) * 2) = v;
                     }
                 }
             }
@@ -412,7 +422,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                 const bool live = ub < g.b_units;
                 const int k = live ? ub / OCT : 0, oct = live ? ub % OCT : 0;
                 w_goff[u] = ((long long)(k0 + k) * g.cg + oct * 8) * (TAPS > 0 ? TAPS : 1);
-                w_dst[u] = live ? (oct * KT + k) * 16 : -1;
+                w_dst[u] = live ? oct * WOP + k * 16 : -1;
             }
         }
         const bool fast_wave = __builtin_amdgcn_ballot_w64(!fast_lane) == 0ull;
@@ -499,7 +509,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                         __builtin_amdgcn_sched_barrier(0);
                         if (w_dst[u] >= 0) {
 #pragma unroll
-                            for (int tap = 0; tap < TAPS; ++tap) *(u32x4*)(ws + tap * OCT * KT * 16 + w_dst[u]) = o[tap];
+                            for (int tap = 0; tap < TAPS; ++tap) *(u32x4*)(ws + tap * OCT * WOP + w_dst[u]) = o[tap];
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -579,7 +589,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
 #pragma unroll
             for (int sw = 0; sw < NSW; ++sw) xb[tm][sw] = xr[tm] + lds_slot(xl[tm] + sw * a.dil_w) * 16;
         }
-        const int b_lane = ((wn * TN) * 32 + l32 + half * KT) * 16;
+        const int b_lane = ((wn * TN) * 32 + l32) * 16 + half * WOP;
         const bool wave_on = wm < n_ptiles;            // this wave owns at least one live pixel tile
 
         // epilogue constants of this lane's filters: only the loads are issued here; they are turned
@@ -628,7 +638,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                 u32x4 fa[NSET][TM], fb[NSET][TN];
                 auto read_frag = [&](int set, int step, int which) {   // which: 0..TN-1 filters, TN.. pixels
                     const int tap = step / KSTEPS, kk = step % KSTEPS;
-                    if (which < TN) fb[set][which] = *(const u32x4*)(ws + ((tap * OCT + 2 * kk) * KT + which * 32) * 16);
+                    if (which < TN) fb[set][which] = *(const u32x4*)(ws + (tap * OCT + 2 * kk) * WOP + which * 32 * 16);
                     else fa[set][which - TN] = *(const u32x4*)(xs + tap_addr(which - TN, tap) + 2 * kk * oct_bytes);
                 };
 #pragma unroll
@@ -677,7 +687,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                     for (int kk = 0; kk < KSTEPS; ++kk) {
                         u32x4 fa[TM], fb[TN];
 #pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) fb[tn] = *(const u32x4*)(ws + ((tap * OCT + 2 * kk) * KT + tn * 32) * 16);
+                        for (int tn = 0; tn < TN; ++tn) fb[tn] = *(const u32x4*)(ws + (tap * OCT + 2 * kk) * WOP + tn * 32 * 16);
 #pragma unroll
                         for (int tm = 0; tm < TM; ++tm) fa[tm] = *(const u32x4*)(xs + ta[tm] + 2 * kk * oct_bytes);
 #pragma unroll
@@ -930,7 +940,7 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     g.a_units = (int)a_units;
     g.b_units = v.TAPS > 0 ? KT * OCT : 0;
     if (g.b_units > v.UB * threads) return false;
-    const long long xb = (long long)OCT * g.NB * g.PSLOTS * 16 + TRASH_BYTES, wb = (long long)taps * OCT * KT * 16;
+    const long long xb = (long long)OCT * g.NB * g.PSLOTS * 16 + TRASH_BYTES, wb = (long long)taps * OCT * igemm_filter_octet_pitch(KT, OCT);
     if (16 + 2 * (xb + wb) > LDS_LIMIT) return false;
     g.xbytes = (int)xb;
     g.wbytes = (int)wb;
