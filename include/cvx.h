@@ -18,7 +18,9 @@
  *     functions below.  They may be used from one thread at a time.
  *   - All tensor data pointers are DEVICE pointers (HIP global memory of the GPU the handle's
  *     stream belongs to), owned by the caller, packed (no strides), element-aligned.  The library
- *     never allocates, frees or copies device memory and needs no workspace.
+ *     never allocates, frees or copies device memory.  It needs no workspace; given one
+ *     (cvx_set_workspace) it runs faster kernels for some problems (cvx_conv_fwd_query says how
+ *     much they want).
  *   - Compute calls only enqueue work on the handle's stream and return; they do not synchronise.
  *     The output buffer must not overlap any input buffer.
  *   - x, w and y must have the same data type.  Arithmetic: products of the stored values,
@@ -65,6 +67,14 @@ cvx_status_t cvx_create(cvx_handle_t* out, void* hip_stream);
 cvx_status_t cvx_set_stream(cvx_handle_t h, void* hip_stream);
 cvx_status_t cvx_get_stream(cvx_handle_t h, void** hip_stream);
 cvx_status_t cvx_destroy(cvx_handle_t h);
+
+/* Workspace (Sec. IV-A: the find step reports "additional memory required" per algorithm, which the
+ * user then provides).  `workspace` is device memory owned by the caller, 256-byte aligned, of
+ * `bytes` bytes; NULL with 0 bytes removes it.  Compute calls on the handle may overwrite all of it
+ * and read nothing from it that they did not write in the same call; it must not overlap any tensor
+ * of a call, and two calls that share a workspace must not run concurrently (calls on one stream
+ * never do).  The memory must stay valid until the last call that used it has finished. */
+cvx_status_t cvx_set_workspace(cvx_handle_t h, void* workspace, unsigned long long bytes);
 
 /* ---- tensor descriptor: packed 4-D, dims (n,c,h,w) (Sec. IV-A: the user constructs the data
  *      structures for the input/output image tensors).  Filters use (K, C/groups, R, S); a bias or
@@ -135,15 +145,26 @@ cvx_status_t cvx_activation_fwd(cvx_handle_t h, cvx_act_t act, float act_alpha,
                                 cvx_tensor_desc_t yd, void* y);
 
 /* What the library would run for this problem, without running it (the find step of Sec. IV-A
- * reduced to its answer: algorithm name, workspace bytes -- always 0 here).  kernel_name receives
- * a NUL-terminated string of at most name_cap bytes (may be NULL with name_cap 0). */
+ * reduced to its answer: algorithm name and the additional memory it uses).  The answer is for
+ * 16-byte-aligned buffers and a handle whose workspace holds at least *workspace_bytes; with a
+ * smaller workspace (or none) the library runs the kernel of the same name without the "_pk"
+ * suffix, and buffers that are only element-aligned are served by the "direct_*" kernel.
+ * cvx_get_last_kernel names what a compute call actually enqueued.  kernel_name receives a
+ * NUL-terminated string of at most name_cap bytes (may be NULL with name_cap 0). */
 cvx_status_t cvx_conv_fwd_query(cvx_tensor_desc_t xd, cvx_tensor_desc_t wd, cvx_conv_desc_t conv,
                                 cvx_tensor_desc_t yd, char* kernel_name, int name_cap,
                                 unsigned long long* workspace_bytes);
 
-/* Force a kernel family for subsequent compute calls on this handle: 0 = automatic choice,
- * 1 = generic direct kernel only.  For testing and benchmarking the fallback. */
+/* The kernel the last successful compute call on this handle enqueued ("" before the first). */
+cvx_status_t cvx_get_last_kernel(cvx_handle_t h, char* kernel_name, int name_cap);
+
+/* Test and benchmark hooks (no passage of the paper; its auto-tuner, Sec. III-C, plays this role there).
+ * cvx_set_kernel_policy: 0 = automatic choice, 1 = generic direct kernel only.
+ * cvx_debug_pin_kernel: spec "<kernel name>" or "<igemm kernel name>,<images per tile>,<rows per tile>"
+ * makes later compute calls on the handle run exactly that kernel, or fail with
+ * CVX_ERR_UNSUPPORTED if it cannot run the problem; NULL or "" removes the pin. */
 cvx_status_t cvx_set_kernel_policy(cvx_handle_t h, int policy);
+cvx_status_t cvx_debug_pin_kernel(cvx_handle_t h, const char* spec);
 
 const char* cvx_status_string(cvx_status_t s);
 const char* cvx_last_error(void);   /* thread-local detail of the last failing call; never NULL */

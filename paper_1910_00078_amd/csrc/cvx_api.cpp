@@ -10,9 +10,30 @@
 #include <cstring>
 #include <new>
 
+// A plan is kept per problem, so that repeated calls (the steady state of training and serving) skip
+// the kernel search: the key is every field of the problem that the choice depends on.
+struct PlanKey {
+    int dtype, N, C, H, W, K, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w, groups, aligned16, policy, pin_version;
+    size_t workspace_bytes;
+};
+struct PlanSlot {
+    bool valid;
+    PlanKey key;
+    cvx::LaunchPlan plan;
+};
+constexpr int kPlanSlots = 8;
+
 struct cvx_handle_s {
     hipStream_t stream;
     int policy;
+    int cus;                       // compute units of the device current when the handle was made
+    void* workspace;               // caller-owned device memory, may be NULL
+    size_t workspace_bytes;
+    char pin[96];                  // developer pin, "" = none
+    int pin_version;               // bumped whenever the pin changes, so cached plans are not reused across pins
+    const char* last_kernel;       // static string: the kernel the last compute call enqueued
+    PlanSlot slots[kPlanSlots];
+    int next_slot;
 };
 struct cvx_tensor_desc_s {
     int dtype, n, c, h, w;
@@ -87,6 +108,54 @@ cvx_status_t build_problem(cvx_tensor_desc_t xd, cvx_tensor_desc_t wd, cvx_conv_
 
 bool aligned(const void* p, int bytes) { return ((uintptr_t)p % (uintptr_t)bytes) == 0; }
 
+PlanKey make_key(const cvx::ConvArgs& a, bool aligned16, int policy, int pin_version, size_t workspace_bytes)
+{
+    PlanKey k;
+    memset(&k, 0, sizeof k);                      // padding too: keys are compared bytewise
+    k.dtype = a.dtype; k.N = a.N; k.C = a.C; k.H = a.H; k.W = a.W; k.K = a.K; k.R = a.R; k.S = a.S;
+    k.pad_h = a.pad_h; k.pad_w = a.pad_w; k.stride_h = a.stride_h; k.stride_w = a.stride_w;
+    k.dil_h = a.dil_h; k.dil_w = a.dil_w; k.groups = a.groups;
+    k.aligned16 = aligned16 ? 1 : 0; k.policy = policy; k.pin_version = pin_version;
+    k.workspace_bytes = workspace_bytes;
+    return k;
+}
+
+// The plan for this problem on this handle: from the handle's cache, or made now and cached.
+const cvx::LaunchPlan* plan_for(cvx_handle_t h, const cvx::ConvArgs& a, size_t workspace_bytes)
+{
+    const bool aligned16 = (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y) & 15) == 0;
+    const PlanKey key = make_key(a, aligned16, h->policy, h->pin_version, workspace_bytes);
+    for (int i = 0; i < kPlanSlots; ++i)
+        if (h->slots[i].valid && memcmp(&h->slots[i].key, &key, sizeof key) == 0) return &h->slots[i].plan;
+    cvx::PlanEnv env;
+    env.cus = h->cus;
+    env.policy = h->policy;
+    env.aligned16 = aligned16;
+    env.workspace_bytes = workspace_bytes;
+    env.pin = h->pin[0] ? h->pin : nullptr;
+    PlanSlot& slot = h->slots[h->next_slot];
+    slot.valid = false;
+    if (!cvx::make_plan(a, env, &slot.plan)) return nullptr;
+    slot.key = key;
+    slot.valid = true;
+    h->next_slot = (h->next_slot + 1) % kPlanSlots;
+    return &slot.plan;
+}
+
+cvx_status_t enqueue(cvx_handle_t h, const cvx::ConvArgs& a, void* workspace, size_t workspace_bytes)
+{
+    const cvx::LaunchPlan* p = plan_for(h, a, workspace ? workspace_bytes : 0);
+    if (!p) return fail(CVX_ERR_UNSUPPORTED, "the pinned kernel \"%s\" cannot run this problem", h->pin);
+    if (log_enabled())
+        fprintf(stderr, "[cvx] conv_fwd dtype=%d N=%d C=%d H=%d W=%d K=%d R=%d S=%d pad=%d,%d stride=%d,%d dil=%d,%d g=%d -> %s\n",
+                a.dtype, a.N, a.C, a.H, a.W, a.K, a.R, a.S, a.pad_h, a.pad_w, a.stride_h, a.stride_w,
+                a.dil_h, a.dil_w, a.groups, p->name);
+    const hipError_t e = cvx::launch_plan(a, *p, workspace, h->stream);
+    if (e != hipSuccess) return fail(CVX_ERR_LAUNCH, "%s: %s", p->name, hipGetErrorString(e));
+    h->last_kernel = p->name;
+    return CVX_OK;
+}
+
 cvx_status_t run_conv(cvx_handle_t h, cvx_tensor_desc_t xd, const void* x, cvx_tensor_desc_t wd, const void* w,
                       cvx_conv_desc_t cd, cvx_tensor_desc_t bd, const void* bias,
                       const float* scale, const float* shift, const float* mean, const float* var, double eps,
@@ -123,42 +192,50 @@ cvx_status_t run_conv(cvx_handle_t h, cvx_tensor_desc_t xd, const void* x, cvx_t
         const uintptr_t x0 = (uintptr_t)x, x1 = x0 + (uintptr_t)a.N * a.C * a.H * a.W * es;
         const uintptr_t w0 = (uintptr_t)w, w1 = w0 + (uintptr_t)a.K * (a.C / a.groups) * a.R * a.S * es;
         if ((x0 < y1 && y0 < x1) || (w0 < y1 && y0 < w1)) return fail(CVX_ERR_BAD_PARAM, "y overlaps an input buffer");
+        const auto hits_y = [&](const void* p, size_t bytes) {
+            const uintptr_t p0 = (uintptr_t)p;
+            return p && p0 < y1 && y0 < p0 + bytes;
+        };
+        if (hits_y(bias, (size_t)a.K * (a.bias_f32 ? 4 : es)) || hits_y(scale, (size_t)a.K * 4) || hits_y(shift, (size_t)a.K * 4) ||
+            hits_y(mean, (size_t)a.K * 4) || hits_y(var, (size_t)a.K * 4))
+            return fail(CVX_ERR_BAD_PARAM, "y overlaps the bias or a batch-norm array");
+        if (h->workspace && hits_y(h->workspace, h->workspace_bytes)) return fail(CVX_ERR_BAD_PARAM, "y overlaps the workspace");
     }
     a.x = x; a.w = w; a.bias = bias; a.y = y;
     a.act = act; a.alpha = alpha;
 
-    const cvx::KernelChoice kc = cvx::select_kernel(a, h->policy);
-    if (log_enabled())
-        fprintf(stderr, "[cvx] conv_fwd dtype=%d N=%d C=%d H=%d W=%d K=%d R=%d S=%d pad=%d,%d stride=%d,%d dil=%d,%d g=%d -> %s\n",
-                a.dtype, a.N, a.C, a.H, a.W, a.K, a.R, a.S, a.pad_h, a.pad_w, a.stride_h, a.stride_w,
-                a.dil_h, a.dil_w, a.groups, kc.name);
-    hipError_t e;
-    switch (kc.id) {
-    case cvx::KID_IGEMM: e = cvx::launch_igemm(a, h->stream); break;
-    case cvx::KID_STEM:  e = cvx::launch_stem(a, h->stream); break;
-    case cvx::KID_POINTWISE: e = cvx::launch_pointwise(a, h->stream); break;
-    default:             e = cvx::launch_direct(a, h->stream); break;
-    }
-    if (e != hipSuccess) return fail(CVX_ERR_LAUNCH, "%s: %s", kc.name, hipGetErrorString(e));
-    return CVX_OK;
+    return enqueue(h, a, h->workspace, h->workspace_bytes);
 }
 
 }  // namespace
 
 namespace cvx {
 
-KernelChoice select_kernel(const ConvArgs& a, int policy)
+bool make_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
 {
-    const char* name = nullptr;
-    if (policy == 0) {
-        if (pointwise_supported(a, &name)) return {KID_POINTWISE, name};
-        if (stem_supported(a, &name)) return {KID_STEM, name};
-        if (igemm_supported(a, &name)) return {KID_IGEMM, name};
+    if (env.policy == 0) {
+        if (env.pin) {
+            // the pin names one kernel of one family; nothing else may serve the call
+            if (strncmp(env.pin, "pointwise_", 10) == 0) return pointwise_plan(a, env, out);
+            if (strncmp(env.pin, "stem_", 5) == 0) return stem_plan(a, env, out);
+            if (strncmp(env.pin, "igemm_", 6) == 0) return igemm_plan(a, env, out);
+            if (strncmp(env.pin, "direct", 6) == 0) return direct_plan(a, env, out);
+            return false;
+        }
+        if (pointwise_plan(a, env, out)) return true;
+        if (stem_plan(a, env, out)) return true;
+        if (igemm_plan(a, env, out)) return true;
     }
-    switch (a.dtype) {
-    case DT_F32: return {KID_DIRECT, "direct_f32"};
-    case DT_F16: return {KID_DIRECT, "direct_f16"};
-    default:     return {KID_DIRECT, "direct_bf16"};
+    return direct_plan(a, env, out);
+}
+
+hipError_t launch_plan(const ConvArgs& a, const LaunchPlan& p, void* workspace, hipStream_t s)
+{
+    switch (p.id) {
+    case KID_IGEMM:     return igemm_launch(a, p, workspace, s);
+    case KID_STEM:      return stem_launch(a, p, s);
+    case KID_POINTWISE: return pointwise_launch(a, p, s);
+    default:            return direct_launch(a, p, s);
     }
 }
 
@@ -171,9 +248,50 @@ cvx_status_t cvx_create(cvx_handle_t* out, void* hip_stream)
     if (!out) return fail(CVX_ERR_NULL, "out is NULL");
     cvx_handle_s* h = new (std::nothrow) cvx_handle_s;
     if (!h) return fail(CVX_ERR_BAD_PARAM, "out of host memory");
+    memset(h, 0, sizeof *h);
     h->stream = (hipStream_t)hip_stream;
-    h->policy = 0;
+    h->last_kernel = "";
+    // With a device present: its compute-unit count, and the kernels' LDS limits raised now rather than
+    // inside the first compute call (which may be under stream capture).  Without one (host-only use of
+    // the descriptor and query calls) the MI355X count stands in.
+    h->cus = 256;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+        h->cus = n;
+        (void)cvx::igemm_prepare();
+        (void)cvx::stem_prepare();
+        (void)cvx::pointwise_prepare();
+    }
+    (void)hipGetLastError();
     *out = h;
+    return CVX_OK;
+}
+
+cvx_status_t cvx_set_workspace(cvx_handle_t h, void* workspace, unsigned long long bytes)
+{
+    if (!h) return fail(CVX_ERR_NULL, "handle is NULL");
+    if ((workspace == nullptr) != (bytes == 0)) return fail(CVX_ERR_BAD_PARAM, "workspace pointer and size must both be given or both be zero");
+    if (!aligned(workspace, 256)) return fail(CVX_ERR_ALIGNMENT, "workspace must be 256-byte aligned");
+    h->workspace = workspace;
+    h->workspace_bytes = (size_t)bytes;
+    return CVX_OK;
+}
+
+cvx_status_t cvx_get_last_kernel(cvx_handle_t h, char* kernel_name, int name_cap)
+{
+    if (!h || !kernel_name) return fail(CVX_ERR_NULL, "NULL argument");
+    if (name_cap < 1) return fail(CVX_ERR_BAD_PARAM, "bad name buffer");
+    strncpy(kernel_name, h->last_kernel, (size_t)name_cap - 1);
+    kernel_name[name_cap - 1] = '\0';
+    return CVX_OK;
+}
+
+cvx_status_t cvx_debug_pin_kernel(cvx_handle_t h, const char* spec)
+{
+    if (!h) return fail(CVX_ERR_NULL, "handle is NULL");
+    if (spec && strlen(spec) >= sizeof h->pin) return fail(CVX_ERR_BAD_PARAM, "pin too long");
+    snprintf(h->pin, sizeof h->pin, "%s", spec ? spec : "");
+    ++h->pin_version;
     return CVX_OK;
 }
 
@@ -359,13 +477,24 @@ cvx_status_t cvx_conv_fwd_query(cvx_tensor_desc_t xd, cvx_tensor_desc_t wd, cvx_
     cvx_status_t st = build_problem(xd, wd, conv, yd, &a);
     if (st != CVX_OK) return st;
     if (name_cap < 0 || (name_cap > 0 && !kernel_name)) return fail(CVX_ERR_BAD_PARAM, "bad name buffer");
-    // Pointers are unknown here; assume the 16-byte alignment device allocators give.
-    const cvx::KernelChoice kc = cvx::select_kernel(a, 0);
+    // No pointers here: the answer is for 16-byte-aligned buffers (what device allocators give), the
+    // automatic policy and a workspace as large as the kernel likes.
+    cvx::PlanEnv env;
+    env.cus = 256;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) env.cus = n;
+    (void)hipGetLastError();
+    env.policy = 0;
+    env.aligned16 = true;
+    env.workspace_bytes = ~(size_t)0;
+    env.pin = nullptr;
+    cvx::LaunchPlan plan;
+    cvx::make_plan(a, env, &plan);
     if (kernel_name && name_cap > 0) {
-        strncpy(kernel_name, kc.name, (size_t)name_cap - 1);
+        strncpy(kernel_name, plan.name, (size_t)name_cap - 1);
         kernel_name[name_cap - 1] = '\0';
     }
-    if (workspace_bytes) *workspace_bytes = 0ull;
+    if (workspace_bytes) *workspace_bytes = (unsigned long long)plan.workspace_bytes;
     return CVX_OK;
 }
 

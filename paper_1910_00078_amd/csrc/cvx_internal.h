@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stddef.h>
 
 namespace cvx {
 
@@ -36,20 +37,46 @@ enum KernelId : int {
     KID_COUNT
 };
 
-struct KernelChoice {
-    KernelId id;
-    const char* name;        // static string
+// What a kernel choice may depend on besides the problem itself.  Nothing here is a data pointer: a
+// plan made once serves every later call with the same problem and environment.
+struct PlanEnv {
+    int cus;                  // compute units of the device
+    int policy;               // 0: automatic choice, 1: generic direct kernel only
+    bool aligned16;           // x, w and y are all 16-byte aligned
+    size_t workspace_bytes;   // caller workspace available to the call (0: none)
+    const char* pin;          // developer pin "<variant>[,<NB>,<TH>]", or nullptr
 };
 
-KernelChoice select_kernel(const ConvArgs& a, int policy);
+// The host's decision for one problem: kernel, geometry, launch shape and the workspace it uses.
+struct LaunchPlan {
+    KernelId id;
+    const char* name;         // static string
+    int variant;              // index into the family's variant table
+    unsigned grid_x, grid_y, block;
+    int lds;                  // dynamic LDS bytes
+    size_t workspace_bytes;   // bytes of the caller's workspace the launch uses (0: none)
+    alignas(8) unsigned char geom[288];   // the family's geometry struct (a kernel argument)
+};
 
-hipError_t launch_direct(const ConvArgs& a, hipStream_t s);
-bool igemm_supported(const ConvArgs& a, const char** variant_name);
-hipError_t launch_igemm(const ConvArgs& a, hipStream_t s);
-bool stem_supported(const ConvArgs& a, const char** variant_name);
-hipError_t launch_stem(const ConvArgs& a, hipStream_t s);
-bool pointwise_supported(const ConvArgs& a, const char** variant_name);
-hipError_t launch_pointwise(const ConvArgs& a, hipStream_t s);
+// Each family: plan() returns false if it does not serve the problem; launch() enqueues what plan() decided.
+bool igemm_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
+hipError_t igemm_launch(const ConvArgs& a, const LaunchPlan& p, void* workspace, hipStream_t s);
+bool stem_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
+hipError_t stem_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
+bool pointwise_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
+hipError_t pointwise_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
+bool direct_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
+hipError_t direct_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
+
+// Raises the dynamic-LDS limit of every kernel of a family (once per process; not a stream operation).
+hipError_t igemm_prepare();
+hipError_t stem_prepare();
+hipError_t pointwise_prepare();
+
+// The problem -> kernel choice (the job the paper gives its solvers, Sec. III-A).  False only if a
+// developer pin names a kernel that cannot run the problem.
+bool make_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
+hipError_t launch_plan(const ConvArgs& a, const LaunchPlan& p, void* workspace, hipStream_t s);
 
 hipError_t launch_bias_add(void* y, const void* bias, int dtype, int bias_f32, int N, int K, int HW, hipStream_t s);
 hipError_t launch_activation(void* y, int dtype, int act, float alpha, long long count, hipStream_t s);

@@ -56,13 +56,27 @@ __global__ void __launch_bounds__(256) direct_conv_kernel(ConvArgs a)
     }
 }
 
-hipError_t launch_direct(const ConvArgs& a, hipStream_t s)
+bool direct_plan(const ConvArgs& a, const PlanEnv&, LaunchPlan* out)
 {
     const long long total = (long long)a.N * a.K * a.Ho * a.Wo;
     const bool split = total <= 32768 && a.C / a.groups >= 8;      // latency-bound sizes
     long long blocks = (total * (split ? 8 : 1) + 255) / 256;
     if (blocks > (1 << 20)) blocks = 1 << 20;           // grid-stride loop covers the rest
-    const dim3 grid((unsigned)blocks), block(256);
+    out->id = KID_DIRECT;
+    out->name = a.dtype == DT_F32 ? "direct_f32" : a.dtype == DT_F16 ? "direct_f16" : "direct_bf16";
+    out->variant = split ? 8 : 1;
+    out->grid_x = (unsigned)blocks;
+    out->grid_y = 1;
+    out->block = 256;
+    out->lds = 0;
+    out->workspace_bytes = 0;
+    return true;
+}
+
+hipError_t direct_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s)
+{
+    const dim3 grid(p.grid_x), block(p.block);
+    const bool split = p.variant == 8;
 #define CVX_LAUNCH_DIRECT(DT)                                                                   \
     do {                                                                                        \
         if (split) hipLaunchKernelGGL((direct_conv_kernel<DT, 8>), grid, block, 0, s, a);       \

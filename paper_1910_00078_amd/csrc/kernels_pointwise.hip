@@ -431,9 +431,8 @@ bool plan_variant(const ConvArgs& a, const Variant& v, int cus, Plan* out)
     return true;
 }
 
-bool choose(const ConvArgs& a, Plan* out)
+bool choose(const ConvArgs& a, const PlanEnv& env, Plan* out)
 {
-    if (getenv("CVX_POINTWISE_OFF")) return false;                  // developer switch: use the general kernels
     if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
     if (a.groups != 1 || a.R != 1 || a.S != 1) return false;
     if (a.stride_h != 1 || a.stride_w != 1 || a.pad_h != 0 || a.pad_w != 0) return false;
@@ -442,15 +441,14 @@ bool choose(const ConvArgs& a, Plan* out)
     if ((long long)a.N * HW >= (1LL << 30)) return false;            // flattened pixel index stays in int
     if ((long long)a.N * HW * a.C >= (1LL << 31) || (long long)a.N * HW * a.K >= (1LL << 31)) return false;
     if (a.C % 32) return false;
-    if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y) & 15) return false;
-    const char* want = getenv("CVX_POINTWISE_FORCE");                // developer override: variant name
+    if (!env.aligned16) return false;
     bool found = false;
     Plan best;
     for (int i = 0; i < kNumVariants; ++i) {
         Plan p;
-        if (!plan_variant(a, kVariants[i], 256, &p)) continue;
-        if (want && *want) {
-            if (strcmp(want, kVariants[i].name) == 0) {
+        if (!plan_variant(a, kVariants[i], env.cus, &p)) continue;
+        if (env.pin) {                                               // developer pin: variant name
+            if (strcmp(env.pin, kVariants[i].name) == 0) {
                 *out = p;
                 return true;
             }
@@ -480,28 +478,46 @@ extern "C" int cvx_debug_set_phase_trace_pointwise(unsigned long long* device_bu
 }
 #endif
 
-bool pointwise_supported(const ConvArgs& a, const char** variant_name)
+bool pointwise_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
 {
+    static_assert(sizeof(pw::Geom) <= sizeof(out->geom), "geometry does not fit the plan");
     pw::Plan p;
-    if (!pw::choose(a, &p)) return false;
-    if (variant_name) *variant_name = p.v->name;
+    if (!pw::choose(a, env, &p)) return false;
+    out->id = KID_POINTWISE;
+    out->name = p.v->name;
+    out->variant = (int)(p.v - pw::kVariants);
+    out->grid_x = (unsigned)p.blocks;
+    out->grid_y = (unsigned)p.kblocks;
+    out->block = (unsigned)((p.v->WM * p.v->WN + pw::ND) * 64);
+    out->lds = p.lds;
+    out->workspace_bytes = 0;
+    memcpy(out->geom, &p.g, sizeof p.g);
     return true;
 }
 
-hipError_t launch_pointwise(const ConvArgs& a, hipStream_t s)
+hipError_t pointwise_prepare()
 {
-    pw::Plan p;
-    if (!pw::choose(a, &p)) return hipErrorInvalidValue;
-    auto kern = a.dtype == DT_BF16 ? p.v->kern_bf16 : p.v->kern_f16;
-    static bool raised[pw::kNumVariants][2];
-    const int vi = (int)(p.v - pw::kVariants), di = a.dtype == DT_BF16 ? 0 : 1;
-    if (!raised[vi][di]) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, pw::LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        raised[vi][di] = true;
-    }
-    const dim3 grid((unsigned)p.blocks, (unsigned)p.kblocks), block((p.v->WM * p.v->WN + pw::ND) * 64);
-    hipLaunchKernelGGL(kern, grid, block, p.lds, s, a, p.g);
+    static const hipError_t status = [] {
+        for (int i = 0; i < pw::kNumVariants; ++i) {
+            for (auto kern : {pw::kVariants[i].kern_bf16, pw::kVariants[i].kern_f16}) {
+                hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, pw::LDS_LIMIT);
+                if (e != hipSuccess) return e;
+            }
+        }
+        return hipSuccess;
+    }();
+    return status;
+}
+
+hipError_t pointwise_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s)
+{
+    hipError_t e = pointwise_prepare();
+    if (e != hipSuccess) return e;
+    const pw::Variant& v = pw::kVariants[p.variant];
+    pw::Geom g;
+    memcpy(&g, p.geom, sizeof g);
+    auto kern = a.dtype == DT_BF16 ? v.kern_bf16 : v.kern_f16;
+    hipLaunchKernelGGL(kern, dim3(p.grid_x, p.grid_y), dim3(p.block), p.lds, s, a, g);
     return hipGetLastError();
 }
 

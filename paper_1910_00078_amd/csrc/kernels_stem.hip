@@ -827,7 +827,7 @@ int stem_lds(const StemVariant& v, const StemGeom& g)
     return g.xbytes + g.wbytes + KT * (PT + 8) * 2;
 }
 
-bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
+bool stem_choose(const ConvArgs& a, const PlanEnv& env, const StemVariant** vout, StemGeom* gout)
 {
     if (a.dtype != DT_BF16 && a.dtype != DT_F16) return false;
     if (a.groups != 1) return false;
@@ -837,11 +837,8 @@ bool stem_plan(const ConvArgs& a, const StemVariant** vout, StemGeom* gout)
     if (a.Wo >= 32768 || a.W >= 32768) return false;
     const long long xbytes = (long long)a.N * a.C * a.H * a.W * 2, ybytes = (long long)a.N * a.K * a.Ho * a.Wo * 2;
     if (xbytes >= (1LL << 31) || ybytes >= (1LL << 31)) return false;
-    if (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y) & 15) return false;
-    if (const char* e = getenv("CVX_STEM_OFF")) {
-        if (*e && *e != '0') return false;
-    }
-    const char* want = getenv("CVX_STEM_FORCE");                    // developer override: variant name
+    if (!env.aligned16) return false;
+    const char* want = env.pin;                                     // developer pin: variant name
     for (const StemVariant& v : kStem) {
         const int PT = (v.stream ? STREAM_NCW : 4) * v.TM * 32, KT = v.TN * 32;
         if (want && *want && strcmp(want, v.name) != 0) continue;
@@ -892,42 +889,56 @@ extern "C" int cvx_debug_set_phase_trace_stem(unsigned long long* device_buffer)
 }
 #endif
 
-bool stem_supported(const ConvArgs& a, const char** variant_name)
+bool stem_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
 {
+    static_assert(sizeof(StemGeom) <= sizeof(out->geom), "geometry does not fit the plan");
     const StemVariant* v;
     StemGeom g;
-    if (!stem_plan(a, &v, &g)) return false;
-    if (variant_name) *variant_name = v->name;
-    return true;
-}
-
-hipError_t launch_stem(const ConvArgs& a, hipStream_t s)
-{
-    const StemVariant* v;
-    StemGeom g;
-    if (!stem_plan(a, &v, &g)) return hipErrorInvalidValue;
-    auto kern = a.dtype == DT_BF16 ? v->kern_bf16 : v->kern_f16;
+    if (!stem_choose(a, env, &v, &g)) return false;
     const int lds = stem_lds(*v, g);
-    static bool raised[kNumStem][2];
-    const int vi = (int)(v - kStem), di = a.dtype == DT_BF16 ? 0 : 1;
-    if (!raised[vi][di]) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, v->stream ? STREAM_LDS_LIMIT : STEM_LDS_LIMIT);
-        if (e != hipSuccess) return e;
-        raised[vi][di] = true;
-    }
     // persistent blocks: as many as stay resident at once (LDS decides), each striding through the tiles
     const long long tiles = (long long)a.N * g.row_blocks * g.k_blocks;
     int per_cu = (160 * 1024) / lds;
     if (per_cu > 4) per_cu = 4;
     if (per_cu < 1) per_cu = 1;
-    long long blocks = 256LL * per_cu;
-    if (const char* e = getenv("CVX_STEM_GRID")) {                  // developer override of the block count
-        const long long v2 = atoll(e);
-        if (v2 > 0) blocks = v2;
-    }
+    long long blocks = (long long)env.cus * per_cu;
     if (blocks > tiles) blocks = tiles;
-    const dim3 grid((unsigned)blocks), block(v->stream ? STREAM_THREADS : 256);
-    hipLaunchKernelGGL(kern, grid, block, lds, s, a, g);
+    out->id = KID_STEM;
+    out->name = v->name;
+    out->variant = (int)(v - kStem);
+    out->grid_x = (unsigned)blocks;
+    out->grid_y = 1;
+    out->block = v->stream ? STREAM_THREADS : 256;
+    out->lds = lds;
+    out->workspace_bytes = 0;
+    memcpy(out->geom, &g, sizeof g);
+    return true;
+}
+
+hipError_t stem_prepare()
+{
+    static const hipError_t status = [] {
+        for (int i = 0; i < kNumStem; ++i) {
+            for (auto kern : {kStem[i].kern_bf16, kStem[i].kern_f16}) {
+                hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                   kStem[i].stream ? STREAM_LDS_LIMIT : STEM_LDS_LIMIT);
+                if (e != hipSuccess) return e;
+            }
+        }
+        return hipSuccess;
+    }();
+    return status;
+}
+
+hipError_t stem_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s)
+{
+    hipError_t e = stem_prepare();
+    if (e != hipSuccess) return e;
+    const StemVariant& v = kStem[p.variant];
+    StemGeom g;
+    memcpy(&g, p.geom, sizeof g);
+    auto kern = a.dtype == DT_BF16 ? v.kern_bf16 : v.kern_f16;
+    hipLaunchKernelGGL(kern, dim3(p.grid_x), dim3(p.block), p.lds, s, a, g);
     return hipGetLastError();
 }
 

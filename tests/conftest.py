@@ -7,11 +7,6 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# The library looks for its developer override CVX_IGEMM_FORCE only if the variable exists when the
-# first implicit-GEMM call is made; empty means "no override".  Present from the start, a test can pin
-# a kernel variant for its own calls (test_gpu_parity.test_pinned_eight_wave_variants).
-os.environ.setdefault("CVX_IGEMM_FORCE", "")
-
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")

@@ -48,10 +48,16 @@ def tolerance_ok(gpu: np.ndarray, ref: np.ndarray, dtype: str):
 
 
 def run_gpu(w: wl.ConvWorkload, x, wt, b, *, act=cvx.CVX_ACT_RELU, alpha=0.0, policy=0, bias_f32=False,
-            bn=None, eps=1e-5, use_bias=True):
-    """x, wt, b in storage representation (host).  Returns (y as fp64 host array, kernel name)."""
+            bn=None, eps=1e-5, use_bias=True, workspace=True, pin=None, offsets=(0, 0, 0)):
+    """x, wt, b in storage representation (host).  Returns (y as fp64 host array, name of the kernel the
+    call enqueued).  workspace=False runs without one; pin is the developer kernel pin; offsets moves
+    x, w, y that many elements off their allocations' (16-byte-aligned) starts."""
     import torch
     dx, dw = to_device(x, w.dtype), to_device(wt, w.dtype)
+    if offsets[0]:
+        dx = _shifted(dx, offsets[0])
+    if offsets[1]:
+        dw = _shifted(dw, offsets[1])
     db = None
     if use_bias:
         db = torch.from_numpy(wl.to_f64(b, w.dtype).astype(np.float32)).cuda() if bias_f32 else to_device(b, w.dtype)
@@ -59,14 +65,25 @@ def run_gpu(w: wl.ConvWorkload, x, wt, b, *, act=cvx.CVX_ACT_RELU, alpha=0.0, po
     # every output element starts as NaN: one the kernel never writes fails the comparison instead of
     # showing whatever the allocator left there (possibly an earlier case's correct result)
     y = torch.full((w.N, w.K, w.Ho, w.Wo), float("nan"), dtype=dx.dtype, device="cuda")
+    if offsets[2]:
+        y = _shifted(y, offsets[2], fill=float("nan"))
+    info = {}
+    if pin and workspace is True:
+        # a pinned kernel may want more workspace than the automatic choice the query answers for
+        workspace = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     cvx.conv_fwd_fused(dx, dw, db, pad=w.pad, stride=w.stride, dil=w.dil, groups=w.groups, act=act,
-                       alpha=alpha, bn=dbn, eps=eps, policy=policy, out=y)
+                       alpha=alpha, bn=dbn, eps=eps, policy=policy, out=y, workspace=workspace, pin=pin, info=info)
     torch.cuda.synchronize()
-    plan = cvx.ConvPlan(DT_CODE[w.dtype], (w.N, w.C, w.H, w.W), (w.K, w.C // w.groups, w.R, w.S), w.pad, w.stride,
-                        w.dil, w.groups)
-    name = "direct" if policy == 1 else plan.kernel_name()
-    plan.close()
-    return to_host_f64(y, w.dtype), name
+    return to_host_f64(y, w.dtype), info["kernel"]
+
+
+def _shifted(t, elements: int, fill=0.0):
+    """A contiguous copy of t that starts `elements` elements into a fresh allocation."""
+    import torch
+    buf = torch.full((t.numel() + elements,), fill, dtype=t.dtype, device=t.device)
+    view = buf[elements:].view(t.shape)
+    view.copy_(t)
+    return view
 
 
 def run_oracle(w: wl.ConvWorkload, x, wt, b, *, act=1, alpha=0.0, bn=None, eps=1e-5, use_bias=True):

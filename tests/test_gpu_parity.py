@@ -24,7 +24,7 @@ def check_case(w, *, policy=0, seed=wl.BASE_SEED, **kw):
         % (w.name, w.dtype, w.N, w.C, w.H, w.W, w.K, w.R, w.S, w.pad, w.stride, w.dil, w.groups, policy, kw))
     x, wt, b = wl.make_inputs(w, seed)
     got, name = run_gpu(w, x, wt, b, policy=policy, **kw)
-    okw = {k: v for k, v in kw.items() if k != "bias_f32"}
+    okw = {k: v for k, v in kw.items() if k not in ("bias_f32", "workspace", "pin", "offsets")}
     ref = run_oracle(w, x, wt, b, **okw)
     assert got.shape == ref.shape
     ok, msg = tolerance_ok(got, ref, w.dtype)
@@ -36,6 +36,35 @@ def check_case(w, *, policy=0, seed=wl.BASE_SEED, **kw):
 @pytest.mark.parametrize("name", ["c1", "c2", "c3a", "c3b", "c4", "c5a", "c5b"])
 def test_full_size_configs(name):
     check_case(wl.WORKLOADS[name])
+
+
+def test_full_size_configs_run_the_kernels_built_for_them():
+    """With the workspace the library asks for, at full size, the launch itself reports the kernel."""
+    want = {"c1": "direct_f32", "c2": "igemm_512x64_c16_3x3_pk", "c3a": "pointwise_256x64_c32_r5",
+            "c3b": "pointwise_128x256_c32_r6", "c4": "stem_stream_512x64_k11", "c5a": "igemm_256x64_c32_3x3_pk",
+            "c5b": "igemm_256x128_c16_3x3_pk"}
+    for name, kernel in want.items():
+        assert check_case(wl.WORKLOADS[name]) == kernel, name
+
+
+@pytest.mark.parametrize("name", ["c2", "c5a", "c5b"])
+def test_full_size_configs_without_workspace(name):
+    """No workspace: the kernels that fetch and transpose the filters themselves."""
+    got = check_case(wl.WORKLOADS[name], workspace=False)
+    assert got.startswith("igemm_") and not got.endswith("_pk"), got
+
+
+@pytest.mark.parametrize("which", ["x", "w", "y"])
+@pytest.mark.parametrize("base", ["c2", "c3a", "c4", "c1"])
+def test_buffers_that_are_only_element_aligned(base, which):
+    """A base pointer one element off a 16-byte boundary is not an error: the generic kernel serves
+    the call (the fast kernels want 16-byte-aligned x, w and y)."""
+    w = wl.WORKLOADS[base]
+    if base != "c1":
+        w = wl.small_variant(w, N=2, H=min(w.H, 30), W=min(w.W, 30))
+    off = tuple(1 if which == n else 0 for n in "xwy")
+    name = check_case(w, offsets=off)
+    assert name.startswith("direct_"), name
 
 
 @pytest.mark.parametrize("name", ["c1", "c2", "c4"])
@@ -118,6 +147,12 @@ def test_reduced_shapes_generic_kernel(w):
     check_case(w, policy=1)
 
 
+@pytest.mark.parametrize("w", [w for w in SMALL if w.R == 3 and w.S == 3 and w.dtype != wl.F32],
+                         ids=lambda w: w.name)
+def test_reduced_3x3_shapes_without_workspace(w):
+    check_case(w, workspace=False)
+
+
 PINNED = [
     # name, variant, workload: the eight-wave implicit-GEMM kernels are chosen on their own only for the
     # full-size layers; pinned, their two producer loops (the fixed-load-count one for blocks in the
@@ -131,23 +166,35 @@ PINNED = [
     ("p256x128_stride2", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=64, K=128)),
     ("p256x128_ragged_filters", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=32, K=200)),
     ("p256x128_whole_images", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5a"], N=9, C=128, K=128)),
+    # the packed-filter twins: interior blocks (fixed-count loop), tensor edges and ragged shapes (general loop),
+    # ragged filters and channels (zero-filled by the packing kernel), groups
+    ("pk512_c64_k64", "igemm_512x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=40, W=40)),
+    ("pk512_no_pad", "igemm_512x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=40, W=40, pad=(0, 0))),
+    ("pk512_odd_stages", "igemm_512x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=28, W=28, C=48)),
+    ("pk512_ragged_filters", "igemm_512x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=5, H=28, W=28, K=48)),
+    ("pk512_c32", "igemm_512x64_c32_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=20, W=20, C=72, K=40)),
+    ("pk256x128_stride2", "igemm_256x128_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=64, K=128)),
+    ("pk256x128_ragged_filters", "igemm_256x128_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=32, K=200)),
+    ("pk256x64_c32_images", "igemm_256x64_c32_3x3_pk", wl.small_variant(wl.WORKLOADS["c5a"], N=9, C=128, K=96), (4, 7)),
+    ("pk256x64_c16_ragged_channels", "igemm_256x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c5a"], N=6, C=40, K=64)),
+    ("pk256x64_groups", "igemm_256x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=2, H=14, W=14, C=128, K=256, groups=2)),
+    ("pk128x128_tiny_images", "igemm_128x128_c32_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=9, H=4, W=4, C=64, K=200), (1, 4)),
+    ("pk256x64_f16", "igemm_256x64_c32_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=2, H=14, W=14, dtype=wl.F16)),
 ]
 
 
 @pytest.mark.parametrize("case", PINNED, ids=lambda c: c[0])
 def test_pinned_eight_wave_variants(case):
-    _, variant, w = case
-    PT = 512 if "512x64" in variant else 256
+    variant, w = case[1], case[2]
+    PT = 512 if "512x64" in variant else 128 if "128x128" in variant else 256
     Ho = (w.H + 2 * w.pad[0] - w.dil[0] * (w.R - 1) - 1) // w.stride[0] + 1
     Wo = (w.W + 2 * w.pad[1] - w.dil[1] * (w.S - 1) - 1) // w.stride[1] + 1
     nb, th = (min(w.N, PT // (Ho * Wo)), Ho) if Ho * Wo <= PT else (1, PT // Wo)
+    if len(case) > 3:
+        nb, th = case[3]                      # the largest tile does not fit this variant's LDS
     say("case %s pinned to %s NB=%d TH=%d: N=%d C=%d H=%d W=%d K=%d pad=%s stride=%s" % (case[0], variant, nb, th, w.N, w.C, w.H, w.W, w.K, w.pad, w.stride))
     x, wt, b = wl.make_inputs(w)
-    os.environ["CVX_IGEMM_FORCE"] = "%s,%d,%d" % (variant, nb, th)
-    try:
-        got, name = run_gpu(w, x, wt, b)
-    finally:
-        os.environ["CVX_IGEMM_FORCE"] = ""
+    got, name = run_gpu(w, x, wt, b, pin="%s,%d,%d" % (variant, nb, th))
     assert name == variant
     ok, msg = tolerance_ok(got, run_oracle(w, x, wt, b), w.dtype)
     assert ok, msg
