@@ -41,7 +41,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = False, use_workspace: bool = True):
+def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = False):
     """Time one workload (a name from workloads.WORKLOADS, or a ConvWorkload).  `unfused` runs the
     same operator as three launches -- convolution, bias add, ReLU -- the unfused route of Sec. V."""
     import numpy as np
@@ -56,9 +56,6 @@ def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = Fa
     stream = torch.cuda.current_stream()
     plan = cvx.ConvPlan(DT_CODE[w.dtype], (w.N, w.C, w.H, w.W), (w.K, w.C // w.groups, w.R, w.S),
                         w.pad, w.stride, w.dil, w.groups, stream=stream.cuda_stream)
-    ws_bytes = plan.workspace_bytes() if use_workspace else 0
-    if ws_bytes:
-        plan.set_workspace(torch.empty(ws_bytes, dtype=torch.uint8, device="cuda"))
     dw, db = to_device(wt, w.dtype), to_device(b, w.dtype)
     x0 = to_device(x, w.dtype)
     set_bytes = w.elem_bytes * (w.N * w.C * w.H * w.W + w.N * w.K * w.Ho * w.Wo)

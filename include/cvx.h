@@ -18,9 +18,7 @@
  *     functions below.  They may be used from one thread at a time.
  *   - All tensor data pointers are DEVICE pointers (HIP global memory of the GPU the handle's
  *     stream belongs to), owned by the caller, packed (no strides), element-aligned.  The library
- *     never allocates, frees or copies device memory.  It needs no workspace; given one
- *     (cvx_set_workspace) it runs faster kernels for some problems (cvx_conv_fwd_query says how
- *     much they want).
+ *     never allocates, frees or copies device memory and needs no workspace.
  *   - Compute calls only enqueue work on the handle's stream and return; they do not synchronise.
  *     The output buffer must not overlap any input buffer.
  *   - x, w and y must have the same data type.  Arithmetic: products of the stored values,
@@ -67,14 +65,6 @@ cvx_status_t cvx_create(cvx_handle_t* out, void* hip_stream);
 cvx_status_t cvx_set_stream(cvx_handle_t h, void* hip_stream);
 cvx_status_t cvx_get_stream(cvx_handle_t h, void** hip_stream);
 cvx_status_t cvx_destroy(cvx_handle_t h);
-
-/* Workspace (Sec. IV-A: the find step reports "additional memory required" per algorithm, which the
- * user then provides).  `workspace` is device memory owned by the caller, 256-byte aligned, of
- * `bytes` bytes; NULL with 0 bytes removes it.  Compute calls on the handle may overwrite all of it
- * and read nothing from it that they did not write in the same call; it must not overlap any tensor
- * of a call, and two calls that share a workspace must not run concurrently (calls on one stream
- * never do).  The memory must stay valid until the last call that used it has finished. */
-cvx_status_t cvx_set_workspace(cvx_handle_t h, void* workspace, unsigned long long bytes);
 
 /* ---- tensor descriptor: packed 4-D, dims (n,c,h,w) (Sec. IV-A: the user constructs the data
  *      structures for the input/output image tensors).  Filters use (K, C/groups, R, S); a bias or
@@ -145,11 +135,9 @@ cvx_status_t cvx_activation_fwd(cvx_handle_t h, cvx_act_t act, float act_alpha,
                                 cvx_tensor_desc_t yd, void* y);
 
 /* What the library would run for this problem, without running it (the find step of Sec. IV-A
- * reduced to its answer: algorithm name and the additional memory it uses).  The answer is for
- * 16-byte-aligned buffers and a handle whose workspace holds at least *workspace_bytes; with a
- * smaller workspace (or none) the library runs the kernel of the same name without the "_pk"
- * suffix, and buffers that are only element-aligned are served by the "direct_*" kernel.
- * cvx_get_last_kernel names what a compute call actually enqueued.  kernel_name receives a
+ * reduced to its answer: algorithm name and the additional memory it needs -- always 0 here).
+ * The answer is for 16-byte-aligned buffers; buffers that are only element-aligned are served by
+ * the "direct_*" kernel.  cvx_get_last_kernel names what a compute call actually enqueued.  kernel_name receives a
  * NUL-terminated string of at most name_cap bytes (may be NULL with name_cap 0). */
 cvx_status_t cvx_conv_fwd_query(cvx_tensor_desc_t xd, cvx_tensor_desc_t wd, cvx_conv_desc_t conv,
                                 cvx_tensor_desc_t yd, char* kernel_name, int name_cap,

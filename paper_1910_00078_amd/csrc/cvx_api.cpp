@@ -14,7 +14,6 @@
 // the kernel search: the key is every field of the problem that the choice depends on.
 struct PlanKey {
     int dtype, N, C, H, W, K, R, S, pad_h, pad_w, stride_h, stride_w, dil_h, dil_w, groups, aligned16, policy, pin_version;
-    size_t workspace_bytes;
 };
 struct PlanSlot {
     bool valid;
@@ -27,8 +26,6 @@ struct cvx_handle_s {
     hipStream_t stream;
     int policy;
     int cus;                       // compute units of the device current when the handle was made
-    void* workspace;               // caller-owned device memory, may be NULL
-    size_t workspace_bytes;
     char pin[96];                  // developer pin, "" = none
     int pin_version;               // bumped whenever the pin changes, so cached plans are not reused across pins
     const char* last_kernel;       // static string: the kernel the last compute call enqueued
@@ -108,7 +105,7 @@ cvx_status_t build_problem(cvx_tensor_desc_t xd, cvx_tensor_desc_t wd, cvx_conv_
 
 bool aligned(const void* p, int bytes) { return ((uintptr_t)p % (uintptr_t)bytes) == 0; }
 
-PlanKey make_key(const cvx::ConvArgs& a, bool aligned16, int policy, int pin_version, size_t workspace_bytes)
+PlanKey make_key(const cvx::ConvArgs& a, bool aligned16, int policy, int pin_version)
 {
     PlanKey k;
     memset(&k, 0, sizeof k);                      // padding too: keys are compared bytewise
@@ -116,22 +113,20 @@ PlanKey make_key(const cvx::ConvArgs& a, bool aligned16, int policy, int pin_ver
     k.pad_h = a.pad_h; k.pad_w = a.pad_w; k.stride_h = a.stride_h; k.stride_w = a.stride_w;
     k.dil_h = a.dil_h; k.dil_w = a.dil_w; k.groups = a.groups;
     k.aligned16 = aligned16 ? 1 : 0; k.policy = policy; k.pin_version = pin_version;
-    k.workspace_bytes = workspace_bytes;
     return k;
 }
 
 // The plan for this problem on this handle: from the handle's cache, or made now and cached.
-const cvx::LaunchPlan* plan_for(cvx_handle_t h, const cvx::ConvArgs& a, size_t workspace_bytes)
+const cvx::LaunchPlan* plan_for(cvx_handle_t h, const cvx::ConvArgs& a)
 {
     const bool aligned16 = (((uintptr_t)a.x | (uintptr_t)a.w | (uintptr_t)a.y) & 15) == 0;
-    const PlanKey key = make_key(a, aligned16, h->policy, h->pin_version, workspace_bytes);
+    const PlanKey key = make_key(a, aligned16, h->policy, h->pin_version);
     for (int i = 0; i < kPlanSlots; ++i)
         if (h->slots[i].valid && memcmp(&h->slots[i].key, &key, sizeof key) == 0) return &h->slots[i].plan;
     cvx::PlanEnv env;
     env.cus = h->cus;
     env.policy = h->policy;
     env.aligned16 = aligned16;
-    env.workspace_bytes = workspace_bytes;
     env.pin = h->pin[0] ? h->pin : nullptr;
     PlanSlot& slot = h->slots[h->next_slot];
     slot.valid = false;
@@ -142,15 +137,15 @@ const cvx::LaunchPlan* plan_for(cvx_handle_t h, const cvx::ConvArgs& a, size_t w
     return &slot.plan;
 }
 
-cvx_status_t enqueue(cvx_handle_t h, const cvx::ConvArgs& a, void* workspace, size_t workspace_bytes)
+cvx_status_t enqueue(cvx_handle_t h, const cvx::ConvArgs& a)
 {
-    const cvx::LaunchPlan* p = plan_for(h, a, workspace ? workspace_bytes : 0);
+    const cvx::LaunchPlan* p = plan_for(h, a);
     if (!p) return fail(CVX_ERR_UNSUPPORTED, "the pinned kernel \"%s\" cannot run this problem", h->pin);
     if (log_enabled())
         fprintf(stderr, "[cvx] conv_fwd dtype=%d N=%d C=%d H=%d W=%d K=%d R=%d S=%d pad=%d,%d stride=%d,%d dil=%d,%d g=%d -> %s\n",
                 a.dtype, a.N, a.C, a.H, a.W, a.K, a.R, a.S, a.pad_h, a.pad_w, a.stride_h, a.stride_w,
                 a.dil_h, a.dil_w, a.groups, p->name);
-    const hipError_t e = cvx::launch_plan(a, *p, workspace, h->stream);
+    const hipError_t e = cvx::launch_plan(a, *p, h->stream);
     if (e != hipSuccess) return fail(CVX_ERR_LAUNCH, "%s: %s", p->name, hipGetErrorString(e));
     h->last_kernel = p->name;
     return CVX_OK;
@@ -199,12 +194,11 @@ cvx_status_t run_conv(cvx_handle_t h, cvx_tensor_desc_t xd, const void* x, cvx_t
         if (hits_y(bias, (size_t)a.K * (a.bias_f32 ? 4 : es)) || hits_y(scale, (size_t)a.K * 4) || hits_y(shift, (size_t)a.K * 4) ||
             hits_y(mean, (size_t)a.K * 4) || hits_y(var, (size_t)a.K * 4))
             return fail(CVX_ERR_BAD_PARAM, "y overlaps the bias or a batch-norm array");
-        if (h->workspace && hits_y(h->workspace, h->workspace_bytes)) return fail(CVX_ERR_BAD_PARAM, "y overlaps the workspace");
     }
     a.x = x; a.w = w; a.bias = bias; a.y = y;
     a.act = act; a.alpha = alpha;
 
-    return enqueue(h, a, h->workspace, h->workspace_bytes);
+    return enqueue(h, a);
 }
 
 }  // namespace
@@ -229,10 +223,10 @@ bool make_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
     return direct_plan(a, env, out);
 }
 
-hipError_t launch_plan(const ConvArgs& a, const LaunchPlan& p, void* workspace, hipStream_t s)
+hipError_t launch_plan(const ConvArgs& a, const LaunchPlan& p, hipStream_t s)
 {
     switch (p.id) {
-    case KID_IGEMM:     return igemm_launch(a, p, workspace, s);
+    case KID_IGEMM:     return igemm_launch(a, p, s);
     case KID_STEM:      return stem_launch(a, p, s);
     case KID_POINTWISE: return pointwise_launch(a, p, s);
     default:            return direct_launch(a, p, s);
@@ -264,16 +258,6 @@ cvx_status_t cvx_create(cvx_handle_t* out, void* hip_stream)
     }
     (void)hipGetLastError();
     *out = h;
-    return CVX_OK;
-}
-
-cvx_status_t cvx_set_workspace(cvx_handle_t h, void* workspace, unsigned long long bytes)
-{
-    if (!h) return fail(CVX_ERR_NULL, "handle is NULL");
-    if ((workspace == nullptr) != (bytes == 0)) return fail(CVX_ERR_BAD_PARAM, "workspace pointer and size must both be given or both be zero");
-    if (!aligned(workspace, 256)) return fail(CVX_ERR_ALIGNMENT, "workspace must be 256-byte aligned");
-    h->workspace = workspace;
-    h->workspace_bytes = (size_t)bytes;
     return CVX_OK;
 }
 
@@ -477,8 +461,8 @@ cvx_status_t cvx_conv_fwd_query(cvx_tensor_desc_t xd, cvx_tensor_desc_t wd, cvx_
     cvx_status_t st = build_problem(xd, wd, conv, yd, &a);
     if (st != CVX_OK) return st;
     if (name_cap < 0 || (name_cap > 0 && !kernel_name)) return fail(CVX_ERR_BAD_PARAM, "bad name buffer");
-    // No pointers here: the answer is for 16-byte-aligned buffers (what device allocators give), the
-    // automatic policy and a workspace as large as the kernel likes.
+    // No pointers here: the answer is for 16-byte-aligned buffers (what device allocators give) and the
+    // automatic policy.
     cvx::PlanEnv env;
     env.cus = 256;
     int dev = 0, n = 0;
@@ -486,7 +470,6 @@ cvx_status_t cvx_conv_fwd_query(cvx_tensor_desc_t xd, cvx_tensor_desc_t wd, cvx_
     (void)hipGetLastError();
     env.policy = 0;
     env.aligned16 = true;
-    env.workspace_bytes = ~(size_t)0;
     env.pin = nullptr;
     cvx::LaunchPlan plan;
     cvx::make_plan(a, env, &plan);
@@ -494,7 +477,7 @@ cvx_status_t cvx_conv_fwd_query(cvx_tensor_desc_t xd, cvx_tensor_desc_t wd, cvx_
         strncpy(kernel_name, plan.name, (size_t)name_cap - 1);
         kernel_name[name_cap - 1] = '\0';
     }
-    if (workspace_bytes) *workspace_bytes = (unsigned long long)plan.workspace_bytes;
+    if (workspace_bytes) *workspace_bytes = 0ull;      // no kernel of this library uses a workspace
     return CVX_OK;
 }
 

@@ -43,24 +43,22 @@ struct PlanEnv {
     int cus;                  // compute units of the device
     int policy;               // 0: automatic choice, 1: generic direct kernel only
     bool aligned16;           // x, w and y are all 16-byte aligned
-    size_t workspace_bytes;   // caller workspace available to the call (0: none)
     const char* pin;          // developer pin "<variant>[,<NB>,<TH>]", or nullptr
 };
 
-// The host's decision for one problem: kernel, geometry, launch shape and the workspace it uses.
+// The host's decision for one problem: kernel, geometry and launch shape.
 struct LaunchPlan {
     KernelId id;
     const char* name;         // static string
     int variant;              // index into the family's variant table
     unsigned grid_x, grid_y, block;
     int lds;                  // dynamic LDS bytes
-    size_t workspace_bytes;   // bytes of the caller's workspace the launch uses (0: none)
     alignas(8) unsigned char geom[288];   // the family's geometry struct (a kernel argument)
 };
 
 // Each family: plan() returns false if it does not serve the problem; launch() enqueues what plan() decided.
 bool igemm_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
-hipError_t igemm_launch(const ConvArgs& a, const LaunchPlan& p, void* workspace, hipStream_t s);
+hipError_t igemm_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
 bool stem_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
 hipError_t stem_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
 bool pointwise_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
@@ -76,7 +74,7 @@ hipError_t pointwise_prepare();
 // The problem -> kernel choice (the job the paper gives its solvers, Sec. III-A).  False only if a
 // developer pin names a kernel that cannot run the problem.
 bool make_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
-hipError_t launch_plan(const ConvArgs& a, const LaunchPlan& p, void* workspace, hipStream_t s);
+hipError_t launch_plan(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
 
 hipError_t launch_bias_add(void* y, const void* bias, int dtype, int bias_f32, int N, int K, int HW, hipStream_t s);
 hipError_t launch_activation(void* y, int dtype, int act, float alpha, long long count, hipStream_t s);

@@ -69,7 +69,6 @@ bool direct_plan(const ConvArgs& a, const PlanEnv&, LaunchPlan* out)
     out->grid_y = 1;
     out->block = 256;
     out->lds = 0;
-    out->workspace_bytes = 0;
     return true;
 }
 

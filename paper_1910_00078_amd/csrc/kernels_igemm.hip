@@ -33,7 +33,7 @@ typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+typedef __attribute__((address_space(3))) unsigned char* lds_ptr_t;
 
 // Division of small non-negative integers by a runtime divisor chosen on the host: q = n / d for
 // n, d < 65536 via one multiply-high (m = ceil(2^32 / d); exact while n * d < 2^32).
@@ -59,7 +59,6 @@ struct IgemmGeom {
     int b_units;     // filter loader units per stage (register-transposed path)
     int xbytes, wbytes;   // LDS bytes per stage for input and filters
     FastDiv by_wo, by_w, by_upi, by_nb, by_kblocks, by_rowblocks;
-    const void* wpack;    // packed-filter kernels: the filters as pack_filters_kernel leaves them, else unused
 };
 
 template <int DT>
@@ -126,9 +125,9 @@ __device__ __forceinline__ int lds_slot(int s) { return s + (s >> 3); }
 // stage hands a finished buffer from producers to consumers and a drained one back.
 // 8: four producer waves for the input and four for the filters; 4: four that do both (kernels whose
 // registers do not allow three waves per SIMD: 4x2 register tiles, or several 3x3 loader units per thread).
-__host__ __device__ constexpr int igemm_producer_waves(int TM, int TN, int TAPS, int UA, int UB, bool PACKED)
+__host__ __device__ constexpr int igemm_producer_waves(int TM, int TN, int TAPS, int UA, int UB)
 {
-    return (!PACKED && TM * TN <= 4 && !(TAPS == 9 && (UA > 1 || UB > 1))) ? 8 : 4;
+    return (TM * TN <= 4 && !(TAPS == 9 && (UA > 1 || UB > 1))) ? 8 : 4;
 }
 
 // Filter region of a stage: [tap][octet][filter] x 16 bytes.  The loader's lanes are dealt octet-fastest, so
@@ -140,20 +139,8 @@ __host__ __device__ constexpr int igemm_filter_octet_pitch(int KT, int OCT)
     return KT * 16 + (OCT > 1 ? (128 / OCT < 16 ? 16 : 128 / OCT) : 0);
 }
 
-// Bytes of one stage's filter region.  Packed-filter kernels fill it with whole 1 KiB direct-to-LDS
-// loads, so there it is a multiple of 1 KiB.
-__host__ __device__ constexpr int igemm_filter_stage_bytes(int KT, int OCT, int taps, bool PACKED)
-{
-    return PACKED ? (taps * OCT * igemm_filter_octet_pitch(KT, OCT) + 1023) / 1024 * 1024
-                  : taps * OCT * igemm_filter_octet_pitch(KT, OCT);
-}
-
-// PACKED: the filters come from g.wpack, where pack_filters_kernel has already laid every (filter block,
-// stage) slice out exactly as the LDS filter region wants it; the four producer waves then copy a slice
-// with direct-to-LDS loads (1 KiB per instruction, no registers, no transposition) and only the input
-// goes through the register transpose.
-template <int DT, int WM, int WN, int TM, int TN, int CC, int TAPS, int UA, int UB, bool PACKED>
-__global__ void __launch_bounds__((WM * WN + igemm_producer_waves(TM, TN, TAPS, UA, UB, PACKED)) * 64)
+template <int DT, int WM, int WN, int TM, int TN, int CC, int TAPS, int UA, int UB>
+__global__ void __launch_bounds__((WM * WN + igemm_producer_waves(TM, TN, TAPS, UA, UB)) * 64)
 igemm_kernel(ConvArgs a, IgemmGeom g)
 {
     constexpr int NCW = WM * WN;           // consumer waves
@@ -161,8 +148,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     // SIMD, 168 registers each): four producer waves load the input and four more the filters, which
     // halves each producer's chain of loads, transposes and LDS writes per stage.  The 4x2 kernels
     // need the registers (two waves per SIMD) and keep four producer waves that do both.
-    constexpr int NPW = igemm_producer_waves(TM, TN, TAPS, UA, UB, PACKED);
-    static_assert(!PACKED || TAPS > 0, "packed filters need a compiled filter size");
+    constexpr int NPW = igemm_producer_waves(TM, TN, TAPS, UA, UB);
     constexpr bool SPLIT = NPW == 8;
     constexpr int THREADS = (NCW + NPW) * 64;
     constexpr int PTHREADS = NPW * 64;     // all producer threads (zero fill)
@@ -181,6 +167,13 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
     const bool producer = wave >= NCW;
+#ifdef CVX_PHASE_TRACE
+    if (lane == 0 && g_phase_trace) {
+        // developer build: which SIMD each wave of the block landed on (HW_ID bits 5:4), 4 bits per wave
+        const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4);
+        atomicOr(&g_phase_trace[((size_t)blockIdx.x + 2048) * 32], (unsigned long long)(((hw >> 4) & 3) + 1) << (4 * wave));
+    }
+#endif
     const int taps = TAPS > 0 ? TAPS : a.R * a.S;
     const int HW = a.H * a.W, HoWo = a.Ho * a.Wo;
     const int stage_bytes = g.xbytes + g.wbytes;
@@ -217,7 +210,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
         // =========================================================================================
         const int ptid = tid - NCW * 64;
         const bool input_wave = !SPLIT || wave < NCW + 4;          // wave-uniform role among the producers
-        const bool filter_wave = !PACKED && (!SPLIT || wave >= NCW + 4);
+        const bool filter_wave = !SPLIT || wave >= NCW + 4;
         const int utid = (SPLIT && !input_wave) ? ptid - UTHREADS : ptid;
         const long long x_total = (long long)a.N * a.C * HW;
         const long long w_total = (long long)a.K * g.cg * taps;
@@ -264,32 +257,6 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             u32x4 rbv[UB][BROWS];
         };
         StageRegs R0;
-
-        // Packed filters: stage `st` of this filter block is one contiguous slice of g.wpack with the
-        // layout of the LDS filter region, NKIB whole KiB; KiB j is copied by producer wave j % 4 with one
-        // instruction that moves 16 bytes per lane straight into LDS (the issuing wave's load counter
-        // covers it).  Every wave issues the same number of them, NDMA, so that the waits below can count:
-        // a wave whose last one has no KiB left copies the slice's first KiB into the input region's trash
-        // slots instead, which nothing reads.
-        constexpr int WBYTES_P = igemm_filter_stage_bytes(KT, OCT, TAPS > 0 ? TAPS : 1, true);
-        constexpr int NKIB = WBYTES_P / 1024;
-        constexpr int NDMA = (NKIB + 3) / 4;
-        static_assert(TRASH_BYTES == 1024, "the trash slots take one copy instruction");
-        auto dma_filters = [&](int st, int buf) __attribute__((always_inline)) {
-            if constexpr (PACKED) {
-                const int pw = wave - NCW;                       // 0..3, wave-uniform
-                const unsigned char* src = (const unsigned char*)g.wpack + ((size_t)kb * g.n_stages + st) * WBYTES_P + lane * 16;
-                unsigned char* xs = smem + BUF0 + buf * stage_bytes;
-#pragma unroll
-                for (int i = 0; i < NDMA; ++i) {
-                    const int j = i * 4 + pw;
-                    const bool real = j < NKIB;
-                    __builtin_amdgcn_global_load_lds((const void*)(src + (real ? j * 1024 : 0)),
-                                                     (__attribute__((address_space(3))) void*)(lds_byte_t*)(xs + (real ? g.xbytes + j * 1024 : g.xbytes - TRASH_BYTES)),
-                                                     16, 0, 0);
-                }
-            }
-        };
 
         // Global loads only; nothing here consumes a loaded value, so all of a stage's loads are in
         // flight together and are first waited on in store_stage.
@@ -469,7 +436,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
         const bool fast_wave = __builtin_amdgcn_ballot_w64(!fast_lane) == 0ull;
 
         auto run_fast = [&]() __attribute__((always_inline)) {
-            constexpr bool DO_X = true, DO_W = !PACKED;
+            constexpr bool DO_X = true, DO_W = true;
             u32x4 xa[2][UA][8];
             u32x4 wb[2][UB][BROWS];
             const int last = g.n_stages - 1;
@@ -558,38 +525,20 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             };
             const std::integral_constant<int, 0> s0;
             const std::integral_constant<int, 1> s1;
-            // Packed filters: the copy of a stage is issued first thing in the half-iteration that builds the
-            // stage (its buffer is free from then on) and must have landed before the barrier that
-            // publishes the buffer; the only loads this wave issues after it are the UA * 8 refill loads, so
-            // "at most that many outstanding" is exactly "the copy is done".
-            auto copy_landed = [&](auto refill_c) __attribute__((always_inline)) {
-                if constexpr (PACKED) {
-                    if constexpr (decltype(refill_c)::value) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(UA * 8) : "memory");
-                    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                }
-            };
             load(0, s0);
             load(1, s1);
-            dma_filters(0, 0);
             prepare_lds();
             __syncthreads();                           // (A) zero fill complete
             const std::true_type refill;
             step(0, s0, 2, refill);                    // stage 0 into LDS, stage 2 into its registers
-            copy_landed(refill);
             __syncthreads();                           // (B) stage 0 is in LDS
             for (int st = 0; st + 2 < g.n_stages; st += 2) {
-                dma_filters(st + 1, 1);
                 step(1, s1, st + 3, refill);           // stage st+1
-                copy_landed(refill);
                 __syncthreads();                       // stage st consumed, stage st+1 in LDS
-                dma_filters(st + 2, 0);
                 step(0, s0, st + 4, refill);           // stage st+2
-                copy_landed(refill);
                 __syncthreads();                       // stage st+1 consumed, stage st+2 in LDS
             }
-            dma_filters(last, 1);
             step(1, s1, 0, std::false_type());         // the last stage; nothing follows it
-            copy_landed(std::false_type());
             __syncthreads();
             __syncthreads();                           // the consumers' barrier after the last stage
         };
@@ -601,22 +550,16 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             // transpose): one register set; the loads of stage st+2 are issued once stage st+1 has been
             // transposed out of it
             load_stage(0, R0);
-            dma_filters(0, 0);
             prepare_lds();
             __syncthreads();                               // (A) zero fill complete
             store_stage(0, 0, R0);
             if (g.n_stages > 1) load_stage(1, R0);
-            if constexpr (PACKED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the filter copy has landed
             __syncthreads();                               // (B) stage 0 is in LDS
             CVX_TRACE_MARK_T(2, NCW * 64);
             for (int st = 0; st < g.n_stages; ++st) {
                 if (st + 1 < g.n_stages) {
-                    dma_filters(st + 1, (st + 1) & 1);     // first, so it has the whole stage to arrive
                     store_stage(st + 1, (st + 1) & 1, R0);
                     if (st + 2 < g.n_stages) load_stage(st + 2, R0);
-                    // the copy must be in LDS before the barrier publishes the buffer (this loop has no
-                    // fixed load count to wait by, so it waits for the newer register loads as well)
-                    if constexpr (PACKED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 }
                 if (st < 6) CVX_TRACE_MARK_T(4 + 2 * st, NCW * 64);
                 __syncthreads();                           // stage st consumed, stage st+1 in LDS
@@ -685,53 +628,92 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
         // first TM+TN MFMAs of a step, one fragment of the NEXT step is read (filters first, then
         // pixels in the order the MFMAs will want them), so LDS latency hides behind the matrix pipe
         // and the waits the compiler inserts are partial.
+        // The consumer loop of the compiled filter sizes.  This wave is the only one on its SIMD that feeds
+        // the matrix pipe, so whatever it issues between two MFMAs besides LDS reads is paid for in
+        // matrix-pipe time: an address add that the next read has to wait for, a branch around an MFMA.
+        // Hence: no branches in the loop; the filter fragments hang off one address register (wa) by
+        // immediate offsets; and the addresses of a k-step's pixel fragments are computed a whole k-step
+        // before their reads are issued (one add each, nothing waits for it).
+        const int lds0 = (int)(uintptr_t)(lds_ptr_t)smem;          // LDS byte address of the dynamic allocation
+        auto lds_read128 = [](int addr) __attribute__((always_inline)) {
+            return *(const __attribute__((address_space(3))) u32x4*)(uintptr_t)(uint32_t)addr;
+        };
+        int wa = lds0 + (int)(BUF0 + g.xbytes + b_lane);
         auto compute_stage = [&](int buf) {
             if (!wave_on) return;
             const unsigned char* xs = smem + BUF0 + buf * stage_bytes;
             const unsigned char* ws = xs + g.xbytes + b_lane;
             if constexpr (TAPS == 9 || TAPS == 1) {
                 constexpr int NS = TAPS * KSTEPS;
-                auto tap_addr = [&](int tm, int tap) {            // tap is a compile-time constant here
-                    return xb[tm][TAPS == 9 ? tap % 3 : 0] + (TAPS == 9 ? tap / 3 : 0) * row_bytes;
-                };
+                const int xs_off = lds0 + BUF0 + buf * stage_bytes;
                 // Fragments are read PF k-steps ahead of their MFMAs.  A step of 2x2 tiles is only
                 // 4 MFMAs (128 clocks), shorter than the LDS latency under load, so those variants look
                 // two steps ahead (three register sets); 4x2 tiles cover the latency with one.
                 constexpr int PF = (TM * TN <= 4 && NS >= 3) ? 2 : 1;
-                constexpr bool SKIP_DEAD_TILES = TM * TN >= 8;
                 constexpr int NSET = PF + 1;
+                constexpr bool SKIP_DEAD_TILES = TM * TN >= 8;
+                const bool last_tile_live = (TM - 1) * WM + wm < n_ptiles;
                 u32x4 fa[NSET][TM], fb[NSET][TN];
+                int pa[TM];                                       // addresses of the pixel fragments of one k-step
+                auto pixel_addresses = [&](int step) {
+                    const int tap = step / KSTEPS, kk = step % KSTEPS;
+                    const int soff = xs_off + (TAPS == 9 ? tap / 3 : 0) * row_bytes + 2 * kk * oct_bytes;   // wave-uniform
+#pragma unroll
+                    for (int tm = 0; tm < TM; ++tm) {
+                        pa[tm] = xb[tm][TAPS == 9 ? tap % 3 : 0] + soff;
+                        asm volatile("" : "+v"(pa[tm]));           // computed here, not where it is used
+                    }
+                };
                 auto read_frag = [&](int set, int step, int which) {   // which: 0..TN-1 filters, TN.. pixels
                     const int tap = step / KSTEPS, kk = step % KSTEPS;
-                    if (which < TN) fb[set][which] = *(const u32x4*)(ws + (tap * OCT + 2 * kk) * WOP + which * 32 * 16);
-                    else fa[set][which - TN] = *(const u32x4*)(xs + tap_addr(which - TN, tap) + 2 * kk * oct_bytes);
+                    if (which < TN) fb[set][which] = lds_read128(wa + ((tap * OCT + 2 * kk) * WOP + which * 32 * 16));
+                    else fa[set][which - TN] = lds_read128(pa[which - TN]);
                 };
 #pragma unroll
-                for (int p = 0; p < PF; ++p)
+                for (int p = 0; p < PF; ++p) {
+                    pixel_addresses(p);
 #pragma unroll
                     for (int j = 0; j < TM + TN; ++j) read_frag(p, p, j);
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < NS; ++i) {
                     const int cur = i % NSET, nxt = (i + PF) % NSET;
                     const bool more = i + PF < NS;
                     int issued = 0;
+                    if (more) {
+                        pixel_addresses(i + PF);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
 #pragma unroll
                     for (int tm = 0; tm < TM; ++tm) {
+                        // A pixel tile past the end of the block's pixels (wave-uniform; only a wave's last
+                        // tile can be one) costs no matrix work and no operand traffic: c5b, where 196 of 256
+                        // pixel rows are live, 43.9 -> 40.0 us.  One branch per tile and k-step, not per MFMA;
+                        // the 2x2 kernels do without (there the branches cost what the spared MFMAs save).
+                        // (both branches issue the same reads, so what has been issued stays a compile-time fact)
+                        const bool dead = SKIP_DEAD_TILES && tm == TM - 1 && !last_tile_live;
+                        const int first = issued;
+                        if (!dead) {
 #pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) {
-                            // pixel tiles past the end of the block's pixels (a wave-uniform test) cost no matrix
-                            // work: c5b (196 of 256 pixel rows live) 45.3 -> 42.1 us.  Not in the 2x2 kernels,
-                            // where the extra branches cost more than the spared MFMAs (c5a +0.5 us).
-                            if (!SKIP_DEAD_TILES || tm * WM + wm < n_ptiles)
+                            for (int tn = 0; tn < TN; ++tn) {
                                 acc[tm][tn] = mfma_32x32x16<DT>(fa[cur][tm], fb[cur][tn], acc[tm][tn]);
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (more && issued < TM + TN) {
-                                read_frag(nxt, i + PF, issued);
-                                ++issued;
                                 __builtin_amdgcn_sched_barrier(0);
+                                if (more && first + tn < TM + TN) {
+                                    read_frag(nxt, i + PF, first + tn);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                            }
+                        } else {
+#pragma unroll
+                            for (int tn = 0; tn < TN; ++tn) {
+                                if (more && first + tn < TM + TN) {
+                                    read_frag(nxt, i + PF, first + tn);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
                             }
                         }
+                        issued = first + TN < TM + TN ? first + TN : TM + TN;
                     }
 #pragma unroll
                     for (int j = 0; j < TM + TN; ++j) {
@@ -742,6 +724,7 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                         }
                     }
                 }
+                wa += buf ? -stage_bytes : stage_bytes;
             } else {
                 int r = 0, s = 0;
                 for (int tap = 0; tap < taps; ++tap) {
@@ -791,12 +774,33 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
             }
+#ifdef CVX_PHASE_TRACE
+        long long tr_mul = 0, tr_bar = 0, tr_first = 0;      // developer build: shader clocks spent multiplying / at the barrier
+#endif
         for (int st = 0; st < g.n_stages; ++st) {
+#ifdef CVX_PHASE_TRACE
+            const long long tq0 = clock64();
+#endif
             compute_stage(st & 1);
             if (st < 6) CVX_TRACE_MARK(3 + 2 * st);
+#ifdef CVX_PHASE_TRACE
+            const long long tq1 = clock64();
+#endif
             __syncthreads();
+#ifdef CVX_PHASE_TRACE
+            tr_mul += tq1 - tq0;
+            tr_bar += clock64() - tq1;
+            if (st == 0) tr_first = tq1 - tq0;
+#endif
         }
         CVX_TRACE_MARK(14);
+#ifdef CVX_PHASE_TRACE
+        if (threadIdx.x == 0 && g_phase_trace) {
+            g_phase_trace[(size_t)blockIdx.x * 32 + 16 + 10] = tr_mul;
+            g_phase_trace[(size_t)blockIdx.x * 32 + 16 + 11] = tr_bar;
+            g_phase_trace[(size_t)blockIdx.x * 32 + 16 + 12] = tr_first;
+        }
+#endif
 
         // ---- epilogue, part 1: batch-norm / activation on the accumulators in registers, one
         //      rounding to the output type, then the tile goes into LDS as [filter][pixel].
@@ -918,66 +922,6 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
 }
 
 // ------------------------------------------------------------------------------------------------
-// Filter packing.  In the kernels above every pixel block that shares a filter block fetches and
-// transposes the same filter slices again (c5a: 32 times, c5b: 128 times), 16 bytes at a time from 64
-// different cache lines per load instruction.  With a workspace the transposition is done once, by
-// this kernel, into the exact byte image of the LDS filter region of every (filter block, stage):
-//   out[(kb * n_stages + st) * stage_bytes + (tap * OCT + oct) * octet_pitch + kl * 16 + j * 2]
-//       = W[first filter of block kb + kl][st * CC + oct * 8 + j][tap]      (0 past the group's filters / channels)
-// One thread per (filter, channel octet): 8 channels x TAPS taps are contiguous in KCRS order.
-// ------------------------------------------------------------------------------------------------
-struct PackGeom {
-    int cg, kg, KT, OCT, CC, kb_per_group, k_blocks, n_stages, octet_pitch, stage_bytes;
-    long long w_total, units;
-};
-
-template <int TAPS>
-__global__ void __launch_bounds__(256) pack_filters_kernel(const uint16_t* __restrict__ w, unsigned char* __restrict__ out, PackGeom pg)
-{
-    constexpr int BROWS = (8 * TAPS * 2 + 15) / 16;
-    const long long u = (long long)blockIdx.x * 256 + threadIdx.x;      // kl fastest: a wave writes 1 KiB runs
-    if (u >= pg.units) return;
-    const int kl = (int)(u % pg.KT);
-    long long t = u / pg.KT;
-    const int oct = (int)(t % pg.OCT);
-    t /= pg.OCT;
-    const int st = (int)(t % pg.n_stages);
-    const int kb = (int)(t / pg.n_stages);
-    const int grp = kb / pg.kb_per_group;
-    const int k = grp * pg.kg + (kb - grp * pg.kb_per_group) * pg.KT + kl;
-    const int c0 = st * pg.CC + oct * 8;
-    const bool k_ok = k < (grp + 1) * pg.kg;
-    const long long off0 = ((long long)k * pg.cg + c0) * TAPS;
-    u32x4 r[BROWS];
-    if (k_ok && c0 + 8 <= pg.cg) {
-#pragma unroll
-        for (int i = 0; i < BROWS; ++i) r[i] = load8(w, off0 + i * 8, pg.w_total);
-    } else {
-#pragma unroll
-        for (int i = 0; i < BROWS; ++i) {
-            u32x4 v = {0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int q = i * 8 + e;                  // = j * TAPS + tap
-                if (k_ok && q / TAPS < 8 && c0 + q / TAPS < pg.cg) v[e >> 1] |= ((uint32_t)w[off0 + q]) << ((e & 1) * 16);
-            }
-            r[i] = v;
-        }
-    }
-    unsigned char* dst = out + ((size_t)kb * pg.n_stages + st) * pg.stage_bytes + (size_t)oct * pg.octet_pitch + kl * 16;
-#pragma unroll
-    for (int tap = 0; tap < TAPS; ++tap) {
-        u32x4 o;
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            const int t0 = (2 * m) * TAPS + tap, t1 = (2 * m + 1) * TAPS + tap;
-            o[m] = pack_halves(r[t1 >> 3][(t1 >> 1) & 3], t1 & 1, r[t0 >> 3][(t0 >> 1) & 3], t0 & 1);
-        }
-        *(u32x4*)(dst + (size_t)tap * pg.OCT * pg.octet_pitch) = o;
-    }
-}
-
-// ------------------------------------------------------------------------------------------------
 // host side: tile geometry, variant table, launch
 // ------------------------------------------------------------------------------------------------
 namespace {
@@ -987,17 +931,13 @@ constexpr int LDS_LIMIT = 160 * 1024;
 struct Variant {
     const char* name;
     int WM, WN, TM, TN, CC, TAPS, UA, UB;     // waves / tiles along pixels (M) and filters (N)
-    bool packed;                              // reads the filters from the workspace pack_filters_kernel fills
     void (*kern_bf16)(ConvArgs, IgemmGeom);
     void (*kern_f16)(ConvArgs, IgemmGeom);
 };
 
-#define IGEMM_VARIANT(nm, WM, WN, TM, TN, CC, TAPS, UA, UB)                                                        \
-    {nm, WM, WN, TM, TN, CC, TAPS, UA, UB, false, igemm_kernel<DT_BF16, WM, WN, TM, TN, CC, TAPS, UA, UB, false>, \
-     igemm_kernel<DT_F16, WM, WN, TM, TN, CC, TAPS, UA, UB, false>}
-#define IGEMM_PACKED(nm, WM, WN, TM, TN, CC, TAPS, UA)                                                         \
-    {nm, WM, WN, TM, TN, CC, TAPS, UA, 1, true, igemm_kernel<DT_BF16, WM, WN, TM, TN, CC, TAPS, UA, 1, true>, \
-     igemm_kernel<DT_F16, WM, WN, TM, TN, CC, TAPS, UA, 1, true>}
+#define IGEMM_VARIANT(nm, WM, WN, TM, TN, CC, TAPS, UA, UB)                                          \
+    {nm, WM, WN, TM, TN, CC, TAPS, UA, UB, igemm_kernel<DT_BF16, WM, WN, TM, TN, CC, TAPS, UA, UB>, \
+     igemm_kernel<DT_F16, WM, WN, TM, TN, CC, TAPS, UA, UB>}
 
 // name: igemm_<pixels per block>x<filters per block>_c<channels per stage>_<taps>
 const Variant kVariants[] = {
@@ -1014,13 +954,6 @@ const Variant kVariants[] = {
     IGEMM_VARIANT("igemm_256x64_c64_1x1", 4, 1, 2, 2, 64, 1, 1, 2),
     IGEMM_VARIANT("igemm_128x128_c64_1x1", 2, 2, 2, 2, 64, 1, 1, 4),
     IGEMM_VARIANT("igemm_256x64_c16_any", 4, 1, 2, 2, 16, 0, 2, 1),
-    // packed-filter twins (name + "_pk"): chosen when the caller has given the handle a workspace
-    IGEMM_PACKED("igemm_512x64_c32_3x3_pk", 4, 1, 4, 2, 32, 9, 1),
-    IGEMM_PACKED("igemm_512x64_c16_3x3_pk", 4, 1, 4, 2, 16, 9, 1),
-    IGEMM_PACKED("igemm_256x128_c16_3x3_pk", 4, 1, 2, 4, 16, 9, 1),
-    IGEMM_PACKED("igemm_256x64_c32_3x3_pk", 4, 1, 2, 2, 32, 9, 1),
-    IGEMM_PACKED("igemm_256x64_c16_3x3_pk", 4, 1, 2, 2, 16, 9, 1),
-    IGEMM_PACKED("igemm_128x128_c32_3x3_pk", 2, 2, 2, 2, 32, 9, 1),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -1075,9 +1008,9 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     const long long a_units = (long long)OCT * g.NB * g.UPI;
     if (a_units > (long long)v.UA * threads) return false;
     g.a_units = (int)a_units;
-    g.b_units = (v.TAPS > 0 && !v.packed) ? KT * OCT : 0;
+    g.b_units = v.TAPS > 0 ? KT * OCT : 0;
     if (g.b_units > v.UB * threads) return false;
-    const long long xb = (long long)OCT * g.NB * g.PSLOTS * 16 + TRASH_BYTES, wb = igemm_filter_stage_bytes(KT, OCT, taps, v.packed);
+    const long long xb = (long long)OCT * g.NB * g.PSLOTS * 16 + TRASH_BYTES, wb = (long long)taps * OCT * igemm_filter_octet_pitch(KT, OCT);
     if (16 + 2 * (xb + wb) > LDS_LIMIT) return false;
     g.xbytes = (int)xb;
     g.wbytes = (int)wb;
@@ -1092,8 +1025,6 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     *out = g;
     return true;
 }
-
-size_t pack_bytes(const IgemmGeom& g) { return (size_t)g.k_blocks * g.n_stages * g.wbytes; }
 
 // Relative time estimate in MFMA-clock cycles: rounds of blocks over the compute units, each round
 // costing the busiest wave's MFMA time plus a fixed fill/drain overhead, plus the bytes staged
@@ -1120,14 +1051,6 @@ const Variant* find_variant(const char* name, size_t len)
     return nullptr;
 }
 
-// The packed-filter twin of a variant (same tile shape), or nullptr.
-const Variant* packed_twin(const Variant& v)
-{
-    char nm[96];
-    snprintf(nm, sizeof nm, "%s_pk", v.name);
-    return find_variant(nm, strlen(nm));
-}
-
 void fill_plan(const ConvArgs& a, const Variant& v, const IgemmGeom& g, LaunchPlan* out)
 {
     static_assert(sizeof(IgemmGeom) <= sizeof(out->geom), "geometry does not fit the plan");
@@ -1136,9 +1059,8 @@ void fill_plan(const ConvArgs& a, const Variant& v, const IgemmGeom& g, LaunchPl
     out->variant = (int)(&v - kVariants);
     out->grid_x = (unsigned)(g.row_blocks * g.img_blocks * g.k_blocks);
     out->grid_y = 1;
-    out->block = (unsigned)((v.WM * v.WN + igemm_producer_waves(v.TM, v.TN, v.TAPS, v.UA, v.UB, v.packed)) * 64);
+    out->block = (unsigned)((v.WM * v.WN + igemm_producer_waves(v.TM, v.TN, v.TAPS, v.UA, v.UB)) * 64);
     out->lds = lds_bytes(v, g);
-    out->workspace_bytes = v.packed ? pack_bytes(g) : 0;
     memcpy(out->geom, &g, sizeof g);
 }
 
@@ -1178,7 +1100,6 @@ bool igemm_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
         }
         IgemmGeom g;
         if (!plan(a, *v, nb, th, &g)) return false;
-        if (v->packed && pack_bytes(g) > env.workspace_bytes) return false;
         fill_plan(a, *v, g, out);
         return true;
     }
@@ -1187,7 +1108,6 @@ bool igemm_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
     IgemmGeom bg;
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant& v = kVariants[i];
-        if (v.packed) continue;                   // considered below, as the twin of the best plain variant
         const int PT = v.WM * v.TM * 32;
         if (a.Wo > PT) continue;
         const bool multi = HoWo <= PT;           // whole images fit: tile over images
@@ -1206,14 +1126,6 @@ bool igemm_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
         }
     }
     if (!bv) return false;
-    // with a workspace, the same tile shape with packed filters, if the packed copy fits
-    if (const Variant* pk = packed_twin(*bv)) {
-        IgemmGeom g;
-        if (plan(a, *pk, bg.NB, bg.TH, &g) && pack_bytes(g) <= env.workspace_bytes) {
-            fill_plan(a, *pk, g, out);
-            return true;
-        }
-    }
     fill_plan(a, *bv, bg, out);
     return true;
 }
@@ -1232,28 +1144,13 @@ hipError_t igemm_prepare()
     return status;
 }
 
-hipError_t igemm_launch(const ConvArgs& a, const LaunchPlan& p, void* workspace, hipStream_t s)
+hipError_t igemm_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s)
 {
     hipError_t e = igemm_prepare();
     if (e != hipSuccess) return e;
     const Variant& v = kVariants[p.variant];
     IgemmGeom g;
     memcpy(&g, p.geom, sizeof g);
-    if (v.packed) {
-        if (!workspace || ((uintptr_t)workspace & 15)) return hipErrorInvalidValue;
-        PackGeom pg;
-        pg.cg = g.cg; pg.kg = g.kg; pg.KT = v.WN * v.TN * 32; pg.OCT = v.CC / 8; pg.CC = v.CC;
-        pg.kb_per_group = g.kb_per_group; pg.k_blocks = g.k_blocks; pg.n_stages = g.n_stages;
-        pg.octet_pitch = igemm_filter_octet_pitch(pg.KT, pg.OCT);
-        pg.stage_bytes = g.wbytes;
-        pg.w_total = (long long)a.K * g.cg * v.TAPS;
-        pg.units = (long long)g.k_blocks * g.n_stages * pg.OCT * pg.KT;
-        const dim3 pgrid((unsigned)((pg.units + 255) / 256)), pblock(256);
-        hipLaunchKernelGGL(pack_filters_kernel<9>, pgrid, pblock, 0, s, (const uint16_t*)a.w, (unsigned char*)workspace, pg);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        g.wpack = workspace;
-    }
     auto kern = a.dtype == DT_BF16 ? v.kern_bf16 : v.kern_f16;
     hipLaunchKernelGGL(kern, dim3(p.grid_x), dim3(p.block), p.lds, s, a, g);
     return hipGetLastError();

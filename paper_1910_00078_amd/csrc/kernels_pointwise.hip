@@ -490,7 +490,6 @@ bool pointwise_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
     out->grid_y = (unsigned)p.kblocks;
     out->block = (unsigned)((p.v->WM * p.v->WN + pw::ND) * 64);
     out->lds = p.lds;
-    out->workspace_bytes = 0;
     memcpy(out->geom, &p.g, sizeof p.g);
     return true;
 }

@@ -910,7 +910,6 @@ bool stem_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
     out->grid_y = 1;
     out->block = v->stream ? STREAM_THREADS : 256;
     out->lds = lds;
-    out->workspace_bytes = 0;
     memcpy(out->geom, &g, sizeof g);
     return true;
 }

@@ -20,7 +20,7 @@ CVX_ACT_IDENTITY, CVX_ACT_RELU, CVX_ACT_LEAKY_RELU, CVX_ACT_TANH, CVX_ACT_LOGIST
 
 # Every symbol include/cvx.h declares (checked by the CPU test-suite against the header text).
 EXPORTS = [
-    "cvx_create", "cvx_set_stream", "cvx_get_stream", "cvx_destroy", "cvx_set_workspace",
+    "cvx_create", "cvx_set_stream", "cvx_get_stream", "cvx_destroy",
     "cvx_tensor_desc_create", "cvx_tensor_desc_set_4d", "cvx_tensor_desc_get_4d", "cvx_tensor_desc_destroy",
     "cvx_conv_desc_create", "cvx_conv_desc_set_2d", "cvx_conv_desc_set_group_count", "cvx_conv_desc_get_2d",
     "cvx_conv_desc_destroy", "cvx_conv_fwd_output_dim",
@@ -64,7 +64,6 @@ def lib():
             "cvx_bias_add": [vp, vp, vp, vp, vp], "cvx_activation_fwd": [vp, ci, cf, vp, vp],
             "cvx_conv_fwd_query": [vp, vp, vp, vp, ctypes.c_char_p, ci, ctypes.POINTER(ctypes.c_ulonglong)],
             "cvx_set_kernel_policy": [vp, ci],
-            "cvx_set_workspace": [vp, vp, ctypes.c_ulonglong],
             "cvx_get_last_kernel": [vp, ctypes.c_char_p, ci],
             "cvx_debug_pin_kernel": [vp, ctypes.c_char_p],
         }
@@ -120,10 +119,6 @@ def cvx_destroy(h: int) -> None:
 
 def cvx_set_kernel_policy(h: int, policy: int) -> None:
     _check(lib().cvx_set_kernel_policy(h, policy), "cvx_set_kernel_policy")
-
-
-def cvx_set_workspace(h: int, workspace_ptr: Optional[int], nbytes: int) -> None:
-    _check(lib().cvx_set_workspace(h, workspace_ptr or None, nbytes), "cvx_set_workspace")
 
 
 def cvx_get_last_kernel(h: int) -> str:
@@ -246,22 +241,10 @@ class ConvPlan:
         cvx_tensor_desc_set_4d(self.bd, dtype if bias_dtype is None else bias_dtype, 1,
                                w_shape[0] if bias_channels is None else bias_channels, 1, 1)
         self.dtype = dtype
-        self._workspace = None
 
     def kernel_name(self) -> str:
-        """The kernel the library runs for aligned buffers when given the workspace it asks for."""
+        """The kernel the library runs for 16-byte-aligned buffers."""
         return cvx_conv_fwd_query(self.xd, self.wd, self.cd, self.yd)[0]
-
-    def workspace_bytes(self) -> int:
-        return cvx_conv_fwd_query(self.xd, self.wd, self.cd, self.yd)[1]
-
-    def set_workspace(self, tensor) -> None:
-        """tensor: a device buffer (torch uint8 tensor) the caller keeps alive, or None."""
-        self._workspace = tensor
-        if tensor is None:
-            cvx_set_workspace(self.h, None, 0)
-        else:
-            cvx_set_workspace(self.h, tensor.data_ptr(), tensor.numel() * tensor.element_size())
 
     def last_kernel(self) -> str:
         return cvx_get_last_kernel(self.h)
@@ -301,12 +284,11 @@ class ConvPlan:
 
 
 def conv_fwd_fused(x, w, bias=None, *, pad=0, stride=1, dil=1, groups=1, act=CVX_ACT_RELU, alpha=0.0,
-                   bn=None, eps=1e-5, out=None, policy: int = 0, workspace=True, pin: Optional[str] = None,
+                   bn=None, eps=1e-5, out=None, policy: int = 0, pin: Optional[str] = None,
                    info: Optional[dict] = None):
     """y = act(bn(conv(x, w) + bias)) on device tensors (torch, contiguous NCHW).  bn, if given, is a
     tuple (scale, shift, mean, var) of fp32 device tensors with K values each.  Allocates y with
-    torch unless `out` is given, and (workspace=True) the workspace the library asks for; everything
-    else happens inside libcvx.so.  `pin` is the developer kernel pin; `info`, if a dict, receives
+    torch unless `out` is given; everything else happens inside libcvx.so.  `pin` is the developer kernel pin; `info`, if a dict, receives
     the name of the kernel that ran under "kernel"."""
     import torch
     if not (x.is_cuda and w.is_cuda):
@@ -323,11 +305,6 @@ def conv_fwd_fused(x, w, bias=None, *, pad=0, stride=1, dil=1, groups=1, act=CVX
         cvx_set_kernel_policy(plan.h, policy)
         if pin:
             plan.pin(pin)
-        if workspace is True:
-            nb = plan.workspace_bytes()
-            workspace = torch.empty(nb, dtype=torch.uint8, device=x.device) if nb else None
-        if workspace is not None and workspace is not False:
-            plan.set_workspace(workspace)
         y = out if out is not None else torch.empty(plan.y_shape, dtype=x.dtype, device=x.device)
         if tuple(y.shape) != tuple(plan.y_shape) or not y.is_contiguous() or y.dtype != x.dtype:
             raise ValueError("out has the wrong shape, dtype or layout")
@@ -340,7 +317,4 @@ def conv_fwd_fused(x, w, bias=None, *, pad=0, stride=1, dil=1, groups=1, act=CVX
                         eps, y.data_ptr(), act, alpha)
         if info is not None:
             info["kernel"] = plan.last_kernel()
-        if plan._workspace is not None:
-            # the workspace must outlive the kernels that use it; y's consumer synchronises on the stream anyway
-            plan._workspace.record_stream(torch.cuda.current_stream(x.device))
     return y

@@ -48,9 +48,9 @@ def tolerance_ok(gpu: np.ndarray, ref: np.ndarray, dtype: str):
 
 
 def run_gpu(w: wl.ConvWorkload, x, wt, b, *, act=cvx.CVX_ACT_RELU, alpha=0.0, policy=0, bias_f32=False,
-            bn=None, eps=1e-5, use_bias=True, workspace=True, pin=None, offsets=(0, 0, 0)):
+            bn=None, eps=1e-5, use_bias=True, pin=None, offsets=(0, 0, 0)):
     """x, wt, b in storage representation (host).  Returns (y as fp64 host array, name of the kernel the
-    call enqueued).  workspace=False runs without one; pin is the developer kernel pin; offsets moves
+    call enqueued).  pin is the developer kernel pin; offsets moves
     x, w, y that many elements off their allocations' (16-byte-aligned) starts."""
     import torch
     dx, dw = to_device(x, w.dtype), to_device(wt, w.dtype)
@@ -68,11 +68,8 @@ def run_gpu(w: wl.ConvWorkload, x, wt, b, *, act=cvx.CVX_ACT_RELU, alpha=0.0, po
     if offsets[2]:
         y = _shifted(y, offsets[2], fill=float("nan"))
     info = {}
-    if pin and workspace is True:
-        # a pinned kernel may want more workspace than the automatic choice the query answers for
-        workspace = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     cvx.conv_fwd_fused(dx, dw, db, pad=w.pad, stride=w.stride, dil=w.dil, groups=w.groups, act=act,
-                       alpha=alpha, bn=dbn, eps=eps, policy=policy, out=y, workspace=workspace, pin=pin, info=info)
+                       alpha=alpha, bn=dbn, eps=eps, policy=policy, out=y, pin=pin, info=info)
     torch.cuda.synchronize()
     return to_host_f64(y, w.dtype), info["kernel"]
 

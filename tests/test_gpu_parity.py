@@ -24,7 +24,7 @@ def check_case(w, *, policy=0, seed=wl.BASE_SEED, **kw):
         % (w.name, w.dtype, w.N, w.C, w.H, w.W, w.K, w.R, w.S, w.pad, w.stride, w.dil, w.groups, policy, kw))
     x, wt, b = wl.make_inputs(w, seed)
     got, name = run_gpu(w, x, wt, b, policy=policy, **kw)
-    okw = {k: v for k, v in kw.items() if k not in ("bias_f32", "workspace", "pin", "offsets")}
+    okw = {k: v for k, v in kw.items() if k not in ("bias_f32", "pin", "offsets")}
     ref = run_oracle(w, x, wt, b, **okw)
     assert got.shape == ref.shape
     ok, msg = tolerance_ok(got, ref, w.dtype)
@@ -39,19 +39,12 @@ def test_full_size_configs(name):
 
 
 def test_full_size_configs_run_the_kernels_built_for_them():
-    """With the workspace the library asks for, at full size, the launch itself reports the kernel."""
-    want = {"c1": "direct_f32", "c2": "igemm_512x64_c16_3x3_pk", "c3a": "pointwise_256x64_c32_r5",
-            "c3b": "pointwise_128x256_c32_r6", "c4": "stem_stream_512x64_k11", "c5a": "igemm_256x64_c32_3x3_pk",
-            "c5b": "igemm_256x128_c16_3x3_pk"}
+    """At full size, the launch itself reports the kernel."""
+    want = {"c1": "direct_f32", "c2": "igemm_512x64_c16_3x3", "c3a": "pointwise_256x64_c32_r5",
+            "c3b": "pointwise_128x256_c32_r6", "c4": "stem_stream_512x64_k11", "c5a": "igemm_256x64_c32_3x3",
+            "c5b": "igemm_256x128_c16_3x3"}
     for name, kernel in want.items():
         assert check_case(wl.WORKLOADS[name]) == kernel, name
-
-
-@pytest.mark.parametrize("name", ["c2", "c5a", "c5b"])
-def test_full_size_configs_without_workspace(name):
-    """No workspace: the kernels that fetch and transpose the filters themselves."""
-    got = check_case(wl.WORKLOADS[name], workspace=False)
-    assert got.startswith("igemm_") and not got.endswith("_pk"), got
 
 
 @pytest.mark.parametrize("which", ["x", "w", "y"])
@@ -147,12 +140,6 @@ def test_reduced_shapes_generic_kernel(w):
     check_case(w, policy=1)
 
 
-@pytest.mark.parametrize("w", [w for w in SMALL if w.R == 3 and w.S == 3 and w.dtype != wl.F32],
-                         ids=lambda w: w.name)
-def test_reduced_3x3_shapes_without_workspace(w):
-    check_case(w, workspace=False)
-
-
 PINNED = [
     # name, variant, workload: the eight-wave implicit-GEMM kernels are chosen on their own only for the
     # full-size layers; pinned, their two producer loops (the fixed-load-count one for blocks in the
@@ -166,20 +153,6 @@ PINNED = [
     ("p256x128_stride2", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=64, K=128)),
     ("p256x128_ragged_filters", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=32, K=200)),
     ("p256x128_whole_images", "igemm_256x128_c16_3x3", wl.small_variant(wl.WORKLOADS["c5a"], N=9, C=128, K=128)),
-    # the packed-filter twins: interior blocks (fixed-count loop), tensor edges and ragged shapes (general loop),
-    # ragged filters and channels (zero-filled by the packing kernel), groups
-    ("pk512_c64_k64", "igemm_512x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=40, W=40)),
-    ("pk512_no_pad", "igemm_512x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=40, W=40, pad=(0, 0))),
-    ("pk512_odd_stages", "igemm_512x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=28, W=28, C=48)),
-    ("pk512_ragged_filters", "igemm_512x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=5, H=28, W=28, K=48)),
-    ("pk512_c32", "igemm_512x64_c32_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=3, H=20, W=20, C=72, K=40)),
-    ("pk256x128_stride2", "igemm_256x128_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=64, K=128)),
-    ("pk256x128_ragged_filters", "igemm_256x128_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c5b"], N=3, C=32, K=200)),
-    ("pk256x64_c32_images", "igemm_256x64_c32_3x3_pk", wl.small_variant(wl.WORKLOADS["c5a"], N=9, C=128, K=96), (4, 7)),
-    ("pk256x64_c16_ragged_channels", "igemm_256x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c5a"], N=6, C=40, K=64)),
-    ("pk256x64_groups", "igemm_256x64_c16_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=2, H=14, W=14, C=128, K=256, groups=2)),
-    ("pk128x128_tiny_images", "igemm_128x128_c32_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=9, H=4, W=4, C=64, K=200), (1, 4)),
-    ("pk256x64_f16", "igemm_256x64_c32_3x3_pk", wl.small_variant(wl.WORKLOADS["c2"], N=2, H=14, W=14, dtype=wl.F16)),
 ]
 
 
