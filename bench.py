@@ -1,17 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the fused forward convolution (conv + bias + ReLU) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--all] [--fusion-sweep] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5b] [--no-layers] [--no-cpu]
+                    [--fusion-sweep] [--calibration-copy]
 
 A step is one cvx_conv_fwd_fused call on one batch of synthetic input already resident in HBM.
 Steps rotate over enough disjoint (x, y) buffer sets that the working set exceeds the 256 MiB
 Infinity Cache, so the figures are HBM figures.  The K timed steps are recorded once into HIP
 graphs (so the Python call overhead is not what is measured) and replayed between two HIP events
 on the launch stream, inside a wall-clock bracket with device synchronisation on both sides.
+The same steps are also timed once as plain calls through the C ABI (no graph): `eager_us_per_step`.
 
-Prints ONE JSON line.  `roofline` prices the kernel against the MI355X peak for its bound;
-`cpu_baseline` is the fp64 CPU oracle timed on this host in the same run (a reported baseline,
-not a target); `parity` is the check of the warm-up output against that oracle.
+Prints ONE JSON line.  The headline workload is the largest single-GPU layer of the benchmark
+set (c5b: 29.6 GFLOP, 65 MB); `layers` carries the same measurement for all seven layers.
+`roofline` prices the kernel against the MI355X peak for its bound; `cpu_baseline` is the fp64 CPU
+oracle timed on this host in the same run (a reported baseline, not a target); `parity` is the
+check of the warm-up output and of an output of the timed replay against that oracle.  If a
+parity check fails the line carries "value": null and the exit status is 1.
 """
 from __future__ import annotations
 
@@ -31,6 +36,8 @@ PEAK_HBM_GBS = 8000.0
 ROTATE_BYTES = 1 << 30               # rotate buffer sets over at least this much memory
 RESULTS_DIR = os.path.join(ROOT, "gpurun_out")   # where the per-layer tables are written as JSON
 GRAPH_CHUNK = 250
+LAYERS = ["c1", "c2", "c3a", "c3b", "c4", "c5a", "c5b"]
+HEADLINE = "c5b"
 
 # Which roofline binds each layer (arithmetic intensity against the ridge point of 2516.6 TFLOP/s over
 # 8 TB/s = 315 FLOP/byte): the two 1x1 layers and the stem are HBM-bound, the 3x3 layers MFMA-bound.
@@ -41,10 +48,9 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = False):
+def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = False, eager: bool = False):
     """Time one workload (a name from workloads.WORKLOADS, or a ConvWorkload).  `unfused` runs the
     same operator as three launches -- convolution, bias add, ReLU -- the unfused route of Sec. V."""
-    import numpy as np
     import torch
     import workloads as wl
     from paper_1910_00078_amd import cvx
@@ -61,6 +67,7 @@ def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = Fa
     set_bytes = w.elem_bytes * (w.N * w.C * w.H * w.W + w.N * w.K * w.Ho * w.Wo)
     nsets = min(64, max(2, -(-ROTATE_BYTES // set_bytes)))
     xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    # every output starts as NaN: an element the kernel never writes fails the parity check
     ys = [torch.full(plan.y_shape, float("nan"), dtype=x0.dtype, device="cuda") for _ in range(nsets)]
 
     def step(i):
@@ -90,7 +97,20 @@ def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = Fa
                "sample": "the whole %s workload once (%.2f GFLOP in %.2f s, fp64)" % (name, w.flops / 1e9, dt)}
         ok, msg = tolerance_ok(to_host_f64(ys[0], w.dtype), ref, w.dtype)
         parity = {"ok": bool(ok), "detail": msg}
-        log("[bench] parity %s: %s" % (name, msg))
+        log("[bench] parity %s (warm-up output): %s" % (name, msg))
+
+    eager_ms = None
+    if eager:
+        # the same steps as plain calls through the C ABI: what a caller without graphs pays per call
+        n = min(steps, 500)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            step(i)
+        e1.record()
+        torch.cuda.synchronize()
+        eager_ms = e0.elapsed_time(e1) / n
 
     # record the timed steps into graphs: chunks of GRAPH_CHUNK launches, replayed
     chunk = min(steps, GRAPH_CHUNK)
@@ -110,6 +130,9 @@ def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = Fa
     torch.cuda.current_stream().wait_stream(side)
     graphs[0].replay()                      # one untimed replay (graph upload)
     torch.cuda.synchronize()
+    if check:
+        # the timed replays must write every output again: poison one buffer the replay covers
+        ys[(chunk - 1) % nsets].fill_(float("nan"))
 
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -123,24 +146,37 @@ def time_workload(name, steps: int, warmup: int, check: bool, unfused: bool = Fa
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ev_ms = e0.elapsed_time(e1)
+    if check:
+        ok, msg = tolerance_ok(to_host_f64(ys[(chunk - 1) % nsets], w.dtype), ref, w.dtype)
+        log("[bench] parity %s (output of the timed replay): %s" % (name, msg))
+        parity = {"ok": bool(parity["ok"] and ok), "detail": parity["detail"], "replay_detail": msg}
     plan.close()
     return {"workload": w, "kernel": kernel, "wall_ms_per_step": wall_ms / steps, "event_ms_per_step": ev_ms / steps,
-            "nsets": nsets, "parity": parity, "cpu": cpu}
+            "eager_ms_per_step": eager_ms, "nsets": nsets, "parity": parity, "cpu": cpu}
+
+
+def measured_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 counter runs (profiles/pmc_traffic.json,
+    written by profile_summary.py); None if the layer has no entry.  It is a figure of the commit the
+    profiles were taken at, not of this run."""
+    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if os.path.exists(tpath):
+        return json.load(open(tpath)).get(name)
+    return None
 
 
 def roofline(w, name, ms_kernel):
     bound = BOUND[name]
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "pmc_traffic.json")
-    if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(name)
+    traffic = measured_traffic(name)
+    src = "profiles/pmc_traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB copy)" if traffic else None
     if bound == "hbm":
         ach = w.algorithmic_bytes / (ms_kernel * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                "traffic": traffic}
+                "traffic": traffic, "traffic_source": src}
     ach = w.flops / (ms_kernel * 1e-3) / 1e12
     peak = PEAK_MFMA_16BIT_TFLOPS if bound == "mfma" else PEAK_FP32_TFLOPS
-    return {"bound": bound, "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic}
+    return {"bound": bound, "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic,
+            "traffic_source": src}
 
 
 def fusion_sweep(steps: int):
@@ -169,13 +205,25 @@ def fusion_sweep(steps: int):
     return rows
 
 
+def layer_row(name, rr):
+    w = rr["workload"]
+    ms = rr["event_ms_per_step"]
+    rf = roofline(w, name, ms)
+    return {"workload": name, "kernel": rr["kernel"], "us": ms * 1e3,
+            "eager_us": None if rr["eager_ms_per_step"] is None else rr["eager_ms_per_step"] * 1e3,
+            "tflops": w.flops / (ms * 1e-3) / 1e12, "gbs": w.algorithmic_bytes / (ms * 1e-3) / 1e9,
+            "bound": rf["bound"], "frac": rf["frac"], "traffic": rf["traffic"],
+            "parity_ok": None if rr["parity"] is None else rr["parity"]["ok"]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2")
-    ap.add_argument("--all", action="store_true", help="also time every layer; table to stderr and bench_all.json in the results directory")
+    ap.add_argument("--workload", default=HEADLINE)
+    ap.add_argument("--no-layers", action="store_true", help="time only the headline workload (no `layers` table)")
+    ap.add_argument("--all", action="store_true", help="accepted for compatibility: the table of all layers is the default")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle (no parity check, no cpu_baseline)")
     ap.add_argument("--fusion-sweep", action="store_true",
                     help="also time fused against unfused (conv, bias add, ReLU as three launches) on every layer and "
@@ -202,9 +250,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    r = time_workload(args.workload, args.steps, args.warmup, check=not args.no_cpu)
+    check = not args.no_cpu
+    r = time_workload(args.workload, args.steps, args.warmup, check=check, eager=True)
     w = r["workload"]
     ms = r["event_ms_per_step"]
+    all_ok = r["parity"] is None or r["parity"]["ok"]
     out = {
         "metric": "conv-fwd TFLOP/s (fused bias+ReLU, bf16) and % of MFMA/HBM roofline",
         "value": w.flops / (r["wall_ms_per_step"] * 1e-3) / 1e12,
@@ -222,22 +272,23 @@ def main():
         "cpu_baseline": r["cpu"],
         "parity": r["parity"],
         "event_ms_per_step": ms,
+        "eager_us_per_step": None if r["eager_ms_per_step"] is None else r["eager_ms_per_step"] * 1e3,
     }
 
-    if args.all:
+    if not args.no_layers:
         rows = []
-        for name in ["c1", "c2", "c3a", "c3b", "c4", "c5a", "c5b"]:
-            steps = 200 if name in ("c3a", "c3b", "c4") else 500
-            rr = time_workload(name, steps, 5, check=False)
-            ww = rr["workload"]
-            rf = roofline(ww, name, rr["event_ms_per_step"])
-            row = {"workload": name, "kernel": rr["kernel"], "us": rr["event_ms_per_step"] * 1e3,
-                   "tflops": ww.flops / (rr["event_ms_per_step"] * 1e-3) / 1e12,
-                   "gbs": ww.algorithmic_bytes / (rr["event_ms_per_step"] * 1e-3) / 1e9,
-                   "bound": rf["bound"], "frac": rf["frac"]}
+        for name in LAYERS:
+            if name == args.workload:
+                rr = r
+            else:
+                steps = 300 if name in ("c3a", "c3b", "c4") else 500
+                rr = time_workload(name, steps, 5, check=check, eager=True)
+            row = layer_row(name, rr)
             rows.append(row)
-            log("[bench] %-4s %-28s %9.2f us  %8.1f TFLOP/s  %8.1f GB/s  %s frac %.3f"
-                % (name, row["kernel"], row["us"], row["tflops"], row["gbs"], row["bound"], row["frac"]))
+            all_ok = all_ok and row["parity_ok"] is not False
+            log("[bench] %-4s %-28s %9.2f us (eager %s)  %8.1f TFLOP/s  %8.1f GB/s  %s frac %.3f  parity %s"
+                % (name, row["kernel"], row["us"], "-" if row["eager_us"] is None else "%.2f us" % row["eager_us"],
+                   row["tflops"], row["gbs"], row["bound"], row["frac"], row["parity_ok"]))
         os.makedirs(RESULTS_DIR, exist_ok=True)
         json.dump(rows, open(os.path.join(RESULTS_DIR, "bench_all.json"), "w"), indent=1)
         out["layers"] = rows
@@ -245,7 +296,10 @@ def main():
     if args.fusion_sweep:
         out["fusion_sweep"] = fusion_sweep(200)
 
+    if not all_ok:
+        out["value"] = None            # a wrong kernel produces no throughput figure
     print(json.dumps(out), flush=True)
+    sys.exit(0 if all_ok else 1)
 
 
 if __name__ == "__main__":
