@@ -54,6 +54,7 @@ struct IgemmGeom {
     int PSLOTS;      // physical ones: one spare 16-byte slot after every 8 (see lds_slot)
     int row_blocks, img_blocks, k_blocks;   // k_blocks counts the filter blocks of all groups
     int cg, kg, kb_per_group;              // channels and filters per group (Sec. IV-A grouped convolution); filter blocks per group
+    int xcd_kparts;  // the 8 XCDs split the tile grid into (8 / xcd_kparts) pixel-block ranges x xcd_kparts filter-block ranges
     int n_stages;    // ceil(C / CC)
     int a_units;     // input loader units per stage
     int b_units;     // filter loader units per stage (register-transposed path)
@@ -178,16 +179,27 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     const int HW = a.H * a.W, HoWo = a.Ho * a.Wo;
     const int stage_bytes = g.xbytes + g.wbytes;
 
-    // ---- which tile: consecutive logical ids stay on one XCD (hardware deals blocks round-robin
-    //      over the 8 XCDs), and blocks that share an input tile (differing only in the filter
-    //      block) are neighbours, so the shared tile is fetched into that XCD's L2 once.
-    int lid = blockIdx.x;
+    // ---- which tile.  The hardware deals blocks round-robin over the 8 XCDs, each with its own L2.
+    //      XCD x takes a rectangle of the (pixel block, filter block) grid, chosen on the host so that
+    //      the chip fetches the least from device memory: every XCD reads the input of its pixel blocks
+    //      and the filters of its filter blocks once.  Inside the rectangle, blocks that share an input
+    //      tile (differing only in the filter block) are neighbours.
+    int pb, kb;
     {
-        const int nblk = gridDim.x;
-        if ((nblk & 7) == 0) lid = (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3);
+        const int nblk = gridDim.x, kblocks = (int)g.by_kblocks.d;
+        if ((nblk & 7) == 0) {
+            const int x = blockIdx.x & 7, j = blockIdx.x >> 3;     // XCD, index inside it
+            const int kparts = g.xcd_kparts, pparts = 8 / kparts;
+            const int kpx = kblocks / kparts;                          // filter blocks per XCD
+            const int ppx = (nblk / kblocks) / pparts;                 // pixel blocks per XCD
+            const int pbl = kpx == 1 ? j : j / kpx;
+            pb = (x / kparts) * ppx + pbl;
+            kb = (x % kparts) * kpx + (j - pbl * kpx);
+        } else {
+            pb = kblocks == 1 ? (int)blockIdx.x : (int)blockIdx.x / kblocks;
+            kb = (int)blockIdx.x - pb * kblocks;
+        }
     }
-    const int pb = g.by_kblocks.d == 1u ? lid : lid / (int)g.by_kblocks.d;
-    const int kb = lid - pb * (int)g.by_kblocks.d;
     const int ib = g.by_rowblocks.d == 1u ? pb : pb / (int)g.by_rowblocks.d;
     const int rb = pb - ib * (int)g.by_rowblocks.d;
     // grouped convolution: filter block kb belongs to group grp, which reads input channels
@@ -1020,6 +1032,23 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     g.by_w = fast_div(a.W);
     g.by_upi = fast_div(g.UPI);
     g.by_nb = fast_div(g.NB);
+    // XCD rectangles: p pixel-block ranges x k filter-block ranges, p * k = 8; the chip then fetches about
+    // k * input + p * filters bytes (each XCD its ranges once)
+    g.xcd_kparts = 1;
+    {
+        const long long pblocks = (long long)g.row_blocks * g.img_blocks;
+        const double in_bytes = 2.0 * a.N * a.C * a.H * a.W, w_bytes = 2.0 * a.K * g.cg * taps;
+        double best = 1e300;
+        for (int k = 1; k <= 8; k *= 2) {
+            const int pp = 8 / k;
+            if (g.k_blocks % k || pblocks % pp) continue;
+            const double fetched = k * in_bytes + pp * w_bytes;
+            if (fetched < best) {
+                best = fetched;
+                g.xcd_kparts = k;
+            }
+        }
+    }
     g.by_kblocks = fast_div(g.k_blocks);
     g.by_rowblocks = fast_div(g.row_blocks);
     *out = g;
