@@ -16,7 +16,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_obj")
 LIB = os.path.join(HERE, "libcvx.so")
-SOURCES = ["cvx_api.cpp", "kernels_direct.hip", "kernels_igemm.hip", "kernels_stem.hip", "kernels_pointwise.hip"]
+SOURCES = ["cvx_api.cpp", "kernels_direct.hip", "kernels_igemm.hip", "kernels_stem.hip", "kernels_pointwise.hip",
+           "kernels_tiled_f32.hip"]
 HEADERS = ["cvx_internal.h", "cvx_device.h", os.path.join("..", "..", "include", "cvx.h")]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

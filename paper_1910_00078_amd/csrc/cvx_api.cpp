@@ -213,12 +213,14 @@ bool make_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
             if (strncmp(env.pin, "pointwise_", 10) == 0) return pointwise_plan(a, env, out);
             if (strncmp(env.pin, "stem_", 5) == 0) return stem_plan(a, env, out);
             if (strncmp(env.pin, "igemm_", 6) == 0) return igemm_plan(a, env, out);
+            if (strncmp(env.pin, "tiled_f32_", 10) == 0) return tiled_f32_plan(a, env, out);
             if (strncmp(env.pin, "direct", 6) == 0) return direct_plan(a, env, out);
             return false;
         }
         if (pointwise_plan(a, env, out)) return true;
         if (stem_plan(a, env, out)) return true;
         if (igemm_plan(a, env, out)) return true;
+        if (tiled_f32_plan(a, env, out)) return true;
     }
     return direct_plan(a, env, out);
 }
@@ -229,6 +231,7 @@ hipError_t launch_plan(const ConvArgs& a, const LaunchPlan& p, hipStream_t s)
     case KID_IGEMM:     return igemm_launch(a, p, s);
     case KID_STEM:      return stem_launch(a, p, s);
     case KID_POINTWISE: return pointwise_launch(a, p, s);
+    case KID_TILED_F32: return tiled_f32_launch(a, p, s);
     default:            return direct_launch(a, p, s);
     }
 }
@@ -255,6 +258,7 @@ cvx_status_t cvx_create(cvx_handle_t* out, void* hip_stream)
         (void)cvx::igemm_prepare();
         (void)cvx::stem_prepare();
         (void)cvx::pointwise_prepare();
+        (void)cvx::tiled_f32_prepare();
     }
     (void)hipGetLastError();
     *out = h;

@@ -34,6 +34,7 @@ enum KernelId : int {
     KID_IGEMM,               // MFMA implicit GEMM, 16-bit types
     KID_STEM,                // low-channel strided direct-MFMA kernel
     KID_POINTWISE,           // persistent streaming kernel for 1x1 filters
+    KID_TILED_F32,           // LDS-tiled fp32 kernel on the fp32 matrix instruction
     KID_COUNT
 };
 
@@ -63,6 +64,8 @@ bool stem_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
 hipError_t stem_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
 bool pointwise_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
 hipError_t pointwise_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
+bool tiled_f32_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
+hipError_t tiled_f32_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
 bool direct_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out);
 hipError_t direct_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
 
@@ -70,6 +73,7 @@ hipError_t direct_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t s);
 hipError_t igemm_prepare();
 hipError_t stem_prepare();
 hipError_t pointwise_prepare();
+hipError_t tiled_f32_prepare();
 
 // The problem -> kernel choice (the job the paper gives its solvers, Sec. III-A).  False only if a
 // developer pin names a kernel that cannot run the problem.

@@ -78,6 +78,19 @@ SMALL = [
     _v("c2", name="c2_ragged", N=2, C=24, K=40, H=19, W=23),
     _v("c2", name="c2_f16", N=2, dtype=wl.F16),
     _v("c2", name="c2_f32", N=1, C=16, K=24, H=20, W=20, dtype=wl.F32),
+    # fp32 on the tiled fp32-MFMA kernel: full-width row tiles, ragged channels / filters / widths, stride and
+    # dilation, groups, many small images per tile, and a long reduction (C*R*S = 4608) for the 1e-5 bound
+    _v("c2", name="f32_c2_like", N=2, dtype=wl.F32),
+    _v("c2", name="f32_ragged", N=3, C=20, K=40, H=19, W=23, dtype=wl.F32),
+    _v("c5b", name="f32_stride2", N=2, C=32, K=48, dtype=wl.F32),
+    _v("c2", name="f32_dil2_pad2", N=2, C=16, K=32, H=24, W=22, pad=(2, 2), dil=(2, 2), dtype=wl.F32),
+    _v("c2", name="f32_groups4", N=2, C=64, K=64, H=28, W=28, groups=4, dtype=wl.F32),
+    _v("c5a", name="f32_small_images", N=16, C=32, K=32, dtype=wl.F32),
+    _v("c5a", name="f32_long_reduction", N=4, C=512, K=64, dtype=wl.F32),
+    _v("c3a", name="f32_1x1", N=2, C=64, K=96, H=28, W=28, dtype=wl.F32),
+    _v("c4", name="f32_7x7_stem", N=2, C=3, H=64, W=64, K=48, dtype=wl.F32),
+    _v("c2", name="f32_5x5", N=2, C=16, K=32, H=20, W=20, R=5, S=5, pad=(2, 2), dtype=wl.F32),
+    _v("c2", name="f32_rect_2x3_stride", N=2, C=24, K=24, H=30, W=31, R=2, S=3, pad=(0, 2), stride=(2, 1), dil=(1, 2), dtype=wl.F32),
     _v("c3a", name="c3a_n2", N=2),
     _v("c3b", name="c3b_n2", N=2),
     _v("c3a", name="1x1_ragged", N=3, C=40, K=24, H=13, W=11),
@@ -173,6 +186,18 @@ def test_pinned_eight_wave_variants(case):
     assert ok, msg
 
 
+@pytest.mark.parametrize("variant", ["tiled_f32_256x64_c8_3x3", "tiled_f32_128x64_c8_3x3", "tiled_f32_256x64_c8", "tiled_f32_128x64_c8", "tiled_f32_128x32_c8", "tiled_f32_128x32_c2"])
+def test_pinned_fp32_variants(variant):
+    for w in (wl.small_variant(wl.WORKLOADS["c2"], N=2, C=24, K=72, H=20, W=20, dtype=wl.F32),
+              wl.small_variant(wl.WORKLOADS["c5a"], N=5, C=16, K=16, dtype=wl.F32)):
+        say("case pinned %s: N=%d C=%d H=%d W=%d K=%d" % (variant, w.N, w.C, w.H, w.W, w.K))
+        x, wt, b = wl.make_inputs(w)
+        got, name = run_gpu(w, x, wt, b, pin=variant)
+        assert name == variant
+        ok, msg = tolerance_ok(got, run_oracle(w, x, wt, b), w.dtype)
+        assert ok, msg
+
+
 def test_kernel_families_serve_the_shapes_they_were_built_for():
     want = {"c2": "igemm_", "c3a": "pointwise_", "c3b": "pointwise_", "c4": "stem_", "c5a": "igemm_", "c5b": "igemm_",
             "c1": "direct_"}
@@ -183,6 +208,10 @@ def test_kernel_families_serve_the_shapes_they_were_built_for():
         got = plan.kernel_name()
         plan.close()
         assert got.startswith(prefix), "%s is served by %s" % (name, got)
+    f32 = cvx.ConvPlan(DT_CODE[wl.F32], (32, 64, 56, 56), (64, 64, 3, 3), (1, 1), (1, 1), (1, 1))
+    got = f32.kernel_name()
+    f32.close()
+    assert got.startswith("tiled_f32_"), "fp32 3x3 is served by %s" % got
     grouped = cvx.ConvPlan(DT_CODE[wl.BF16], (2, 128, 14, 14), (128, 32, 3, 3), (1, 1), (1, 1), (1, 1), 4)
     got = grouped.kernel_name()
     grouped.close()
@@ -193,10 +222,12 @@ def test_kernel_families_serve_the_shapes_they_were_built_for():
 @pytest.mark.parametrize("act,alpha", [(cvx.CVX_ACT_IDENTITY, 0.0), (cvx.CVX_ACT_RELU, 0.0),
                                         (cvx.CVX_ACT_LEAKY_RELU, 0.1), (cvx.CVX_ACT_TANH, 0.0),
                                         (cvx.CVX_ACT_LOGISTIC, 0.0)])
-@pytest.mark.parametrize("base", ["c2", "c1", "c4", "c3a"])
+@pytest.mark.parametrize("base", ["c2", "c1", "c4", "c3a", "c2_f32"])
 def test_activations(base, act, alpha):
-    w = wl.WORKLOADS[base]
-    if base != "c1":
+    w = wl.WORKLOADS[base[:2]] if base == "c2_f32" else wl.WORKLOADS[base]
+    if base == "c2_f32":
+        w = wl.small_variant(w, N=2, H=30, W=30, dtype=wl.F32)
+    elif base != "c1":
         w = wl.small_variant(w, N=2, H=min(w.H, 40), W=min(w.W, 40))
     check_case(w, act=act, alpha=alpha)
 
@@ -210,10 +241,12 @@ def test_no_bias_and_fp32_bias(base):
     check_case(w, bias_f32=True)
 
 
-@pytest.mark.parametrize("base", ["c2", "c3b", "c1"])
+@pytest.mark.parametrize("base", ["c2", "c3b", "c1", "c2_f32"])
 def test_batchnorm_epilogue(base):
-    w = wl.WORKLOADS[base]
-    if base != "c1":
+    w = wl.WORKLOADS[base[:2]] if base == "c2_f32" else wl.WORKLOADS[base]
+    if base == "c2_f32":
+        w = wl.small_variant(w, N=2, H=30, W=30, dtype=wl.F32)
+    elif base != "c1":
         w = wl.small_variant(w, N=2)
     rng = np.random.default_rng(5)
     bn = (rng.uniform(0.5, 1.5, w.K), rng.uniform(-0.5, 0.5, w.K), rng.uniform(-0.3, 0.3, w.K),

@@ -84,6 +84,8 @@ WORKLOADS = {
     "c5a": ConvWorkload("c5a", BF16, 128, 512, 7, 7, 512, 3, 3, pad=(1, 1), seed_index=6),
     "c5b": ConvWorkload("c5b", BF16, 128, 256, 28, 28, 256, 3, 3, pad=(1, 1), stride=(2, 2),
                         seed_index=7),
+    # not one of the five configurations: the 56x56 stage layer in fp32, the benchmark row of the fp32 path
+    "c2f32": ConvWorkload("c2f32", F32, 32, 64, 56, 56, 64, 3, 3, pad=(1, 1), seed_index=8),
 }
 
 
