@@ -110,6 +110,37 @@ __device__ __forceinline__ uint32_t max_packed(uint32_t v, uint32_t floor2)
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, v), __builtin_bit_cast(s16x2_t, floor2)));
 }
 
+// ---- vector types, the 16-bit matrix instruction and the packed output conversion, shared by the MFMA kernels
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// v_mfma_f32_32x32x16 (bf16 or f16 in, fp32 accumulate): a and b hold a lane's 8 consecutive reduction elements.
+template <int DT>
+__device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c)
+{
+    if constexpr (DT == DT_BF16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// Two fp32 values -> one dword of two bf16 / fp16 values (lo in bits 0..15), round to nearest even
+// in hardware (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32).
+template <int DT>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi)
+{
+    const f32x2 v = {lo, hi};
+    if constexpr (DT == DT_BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
+
 // Fetches the first BYTES bytes of the kernel-argument segment with a few wide scalar loads that
 // are all in flight together, and waits for them once.  The compiler otherwise fetches arguments
 // where they are first needed, and a kernel prologue that decodes its tile from several of them

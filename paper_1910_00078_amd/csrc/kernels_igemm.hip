@@ -28,11 +28,6 @@
 
 namespace cvx {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) unsigned char* lds_ptr_t;
 
 // Division of small non-negative integers by a runtime divisor chosen on the host: q = n / d for
@@ -62,15 +57,6 @@ struct IgemmGeom {
     FastDiv by_wo, by_w, by_upi, by_nb, by_kblocks, by_rowblocks;
 };
 
-template <int DT>
-__device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c)
-{
-    if constexpr (DT == DT_BF16)
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
-
 // 16-byte load of 8 consecutive 16-bit elements starting at element offset `off` of a tensor with
 // `total` elements; elements outside the tensor read as zero.  Addresses are only 2-byte aligned.
 __device__ __forceinline__ u32x4 load8(const uint16_t* base, long long off, long long total)
@@ -83,19 +69,6 @@ __device__ __forceinline__ u32x4 load8(const uint16_t* base, long long off, long
         if (o >= 0 && o < total) v[e >> 1] |= ((uint32_t)base[o]) << ((e & 1) * 16);
     }
     return v;
-}
-
-// Two fp32 values -> one dword of two bf16 / fp16 values (lo in bits 0..15), round to nearest even
-// in hardware (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32).
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-template <int DT>
-__device__ __forceinline__ uint32_t pack2(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    if constexpr (DT == DT_BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
 // result = (half `hb` of b) | (half `ha` of a) << 16
@@ -1140,7 +1113,17 @@ bool igemm_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
         const int PT = v.WM * v.TM * 32;
         if (a.Wo > PT) continue;
         const bool multi = HoWo <= PT;           // whole images fit: tile over images
-        const int hi = multi ? PT / HoWo : PT / a.Wo;
+        int hi = multi ? PT / HoWo : PT / a.Wo;
+        if (multi) {
+            // no more images per tile than the loader threads and the LDS can take (plan() checks both
+            // exactly; this only keeps the search from walking through hundreds of hopeless sizes)
+            const int OCT = v.CC / 8, PH = (a.Ho - 1) * a.stride_h + (a.R - 1) * a.dil_h + 1;
+            const int WP = (a.W + 2 * a.pad_w + 7) & ~7;
+            const long long upi = ((long long)PH * a.W + 7) / 8, slot_bytes = (long long)PH * WP * 18;
+            const long long by_units = (long long)v.UA * 256 / (OCT * upi), by_lds = (LDS_LIMIT / 2) / (OCT * slot_bytes);
+            if (by_units < hi) hi = (int)by_units;
+            if (by_lds < hi) hi = (int)by_lds;
+        }
         // only tile heights near the top matter: shorter tiles only add blocks
         for (int t = hi, tried = 0; t >= 1 && tried < 12; --t) {
             IgemmGeom g;

@@ -35,14 +35,6 @@ namespace cvx {
 
 namespace pw {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 
@@ -54,23 +46,6 @@ struct Geom {
     int x_streaming;   // 1: input loads carry the nontemporal hint
     int w_off, ca_off, out_off, ring_off;   // LDS byte offsets
 };
-
-template <int DT>
-__device__ __forceinline__ f32x16 mfma(u32x4 a, u32x4 b, f32x16 c)
-{
-    if constexpr (DT == DT_BF16)
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
-
-template <int DT>
-__device__ __forceinline__ uint32_t pack2(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    if constexpr (DT == DT_BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
-}
 
 // Transposing LDS read.  Within each group of 16 lanes, lane s supplies the address of 4 consecutive
 // 16-bit elements; with K = s / 4 and M = 4 * (s % 4) + {0..3} naming those elements, lane i of the
@@ -348,7 +323,7 @@ pointwise_kernel(ConvArgs a, Geom g)
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma<DT>(fa[kk][tm], fb[kk][tn], acc[tm][tn]);
+                    for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma_32x32x16<DT>(fa[kk][tm], fb[kk][tn], acc[tm][tn]);
 
             if (++st == SPT) {
                 st = 0;

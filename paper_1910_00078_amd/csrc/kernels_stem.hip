@@ -26,14 +26,6 @@
 
 namespace cvx {
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4_a2 __attribute__((ext_vector_type(4), aligned(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 struct StemGeom {
     int TH;            // output rows per block (tiles span the full output width)
@@ -49,23 +41,6 @@ struct StemGeom {
     uint32_t upr_magic;
     uint32_t ph_magic;
 };
-
-template <int DT>
-__device__ __forceinline__ f32x16 stem_mfma(u32x4 a, u32x4 b, f32x16 c)
-{
-    if constexpr (DT == DT_BF16)
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
-
-template <int DT>
-__device__ __forceinline__ uint32_t stem_pack2(float lo, float hi)
-{
-    const f32x2 v = {lo, hi};
-    if constexpr (DT == DT_BF16) return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-    else return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
-}
 
 __device__ __forceinline__ int div_small(int n, int d, uint32_t magic) { return d == 1 ? n : (int)__umulhi((uint32_t)n, magic); }
 
@@ -316,7 +291,7 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
                     for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
                         for (int tn = 0; tn < TN; ++tn) {
-                            acc[tm][tn] = stem_mfma<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
+                            acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
                             __builtin_amdgcn_sched_barrier(0);
                             if (more_k && issued < TM + TN) {
                                 read_next();
@@ -355,7 +330,7 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = stem_mfma<DT>(fa[tm], fb[tn], acc[tm][tn]);
+                    for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma_32x32x16<DT>(fa[tm], fb[tn], acc[tm][tn]);
             };
             u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
             read_step(fa0, fb0);
@@ -393,7 +368,7 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
                                 v[j] = act_fn(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t);
                             }
                             const int f = (tm * WAVES + wave) * 32 + 8 * q4 + 4 * half;
-                            *(uint2*)(ot + kl * PTP + f) = make_uint2(stem_pack2<DT>(v[0], v[1]), stem_pack2<DT>(v[2], v[3]));
+                            *(uint2*)(ot + kl * PTP + f) = make_uint2(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]));
                         }
                     }
                 }
@@ -701,7 +676,7 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
                     for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
                         for (int tn = 0; tn < TN; ++tn) {
-                            acc[tm][tn] = stem_mfma<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
+                            acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
                             __builtin_amdgcn_sched_barrier(0);
                             if (more_k && issued < TM + TN) {
                                 read_next();
@@ -743,8 +718,8 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
                             for (int q4 = 0; q4 < 4; ++q4) {
                                 const f32x16& t = acc[tm][tn];
                                 *(uint2*)(ow + l32 * OPITCH + (tm * 32 + 8 * q4 + 4 * half) * 2) =
-                                    make_uint2(max_packed(stem_pack2<DT>(t[4 * q4], t[4 * q4 + 1]), floor2),
-                                               max_packed(stem_pack2<DT>(t[4 * q4 + 2], t[4 * q4 + 3]), floor2));
+                                    make_uint2(max_packed(pack2<DT>(t[4 * q4], t[4 * q4 + 1]), floor2),
+                                               max_packed(pack2<DT>(t[4 * q4 + 2], t[4 * q4 + 3]), floor2));
                             }
                     } else {
 #pragma unroll
@@ -759,7 +734,7 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
                                     v[j] = fmaf(neg_slope, fminf(t, 0.0f), fmaxf(t, 0.0f));
                                 }
                                 *(uint2*)(ow + l32 * OPITCH + (tm * 32 + 8 * q4 + 4 * half) * 2) =
-                                    make_uint2(stem_pack2<DT>(v[0], v[1]), stem_pack2<DT>(v[2], v[3]));
+                                    make_uint2(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]));
                             }
                     }
                     u32x4 o[4];

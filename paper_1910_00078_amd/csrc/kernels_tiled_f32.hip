@@ -34,7 +34,6 @@ struct Geom {
     int xfloats, wfloats;        // LDS floats per buffer for input and filters
 };
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int THREADS = 256;
 constexpr int XE = 16;           // input elements a thread stages per chunk, at most

@@ -175,7 +175,33 @@ def test_kernel_choice_is_host_logic_and_follows_the_shape():
     assert family(v(wl.WORKLOADS["c3a"], H=7, W=7)).startswith("igemm_")             # 49 pixels: not a multiple of 8
     assert family(v(wl.WORKLOADS["c2"], C=128, K=128, groups=4)).startswith("igemm_")
     assert family(v(wl.WORKLOADS["c2"], C=64, K=64, groups=64)).startswith("direct_")  # depthwise
-    assert family(v(wl.WORKLOADS["c2"], dtype=wl.F32)).startswith("direct_")
+    assert family(v(wl.WORKLOADS["c2"], dtype=wl.F32)).startswith("tiled_f32_")         # fp32 of a real size: the fp32 MFMA kernel
+    assert family(v(wl.WORKLOADS["c4"], dtype=wl.F32)).startswith("tiled_f32_")         # any filter size
+
+
+def test_kernel_search_is_cheap_on_the_host():
+    """The problem -> kernel search (cvx_conv_fwd_query runs all of it, uncached, on every call)
+    stays in the microseconds for the benchmark layers and for the shapes that used to make it long
+    (tiny images, where many tile shapes compete).  Compute calls do not even pay this: a handle
+    keeps the plan of the problems it has seen."""
+    import time
+    import workloads as wl
+    code = {wl.F32: cvx.CVX_F32, wl.F16: cvx.CVX_F16, wl.BF16: cvx.CVX_BF16}
+    cases = [wl.WORKLOADS[n] for n in ("c1", "c2", "c3a", "c3b", "c4", "c5a", "c5b")]
+    cases.append(wl.small_variant(wl.WORKLOADS["c5a"], N=4096, H=1, W=1))
+    cases.append(wl.small_variant(wl.WORKLOADS["c5a"], N=4096, H=2, W=2))
+    for w in cases:
+        plan = cvx.ConvPlan(code[w.dtype], (w.N, w.C, w.H, w.W), (w.K, w.C // w.groups, w.R, w.S),
+                            w.pad, w.stride, w.dil, w.groups)
+        L, buf, ws = cvx.lib(), ctypes.create_string_buffer(128), ctypes.c_ulonglong()
+        n = 2000
+        t0 = time.perf_counter()
+        for _ in range(n):
+            L.cvx_conv_fwd_query(plan.xd, plan.wd, plan.cd, plan.yd, buf, 128, ctypes.byref(ws))
+        us = (time.perf_counter() - t0) / n * 1e6
+        plan.close()
+        # ctypes itself costs about a microsecond per call; the bound leaves room for a slow CI host
+        assert us < 25.0, "%s: %.1f us per uncached kernel search" % (w.name, us)
 
 
 def test_out_params_untouched_on_failure():
