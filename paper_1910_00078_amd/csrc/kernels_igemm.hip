@@ -54,7 +54,9 @@ struct IgemmGeom {
     int a_units;     // input loader units per stage
     int b_units;     // filter loader units per stage (register-transposed path)
     int xbytes, wbytes;   // LDS bytes per stage for input and filters
-    FastDiv by_wo, by_w, by_upi, by_nb, by_kblocks, by_rowblocks;
+    int flat;        // output staging: 0 = [filter][pixel] tile; 1, 2 = the tile's run of y, image by image (see the epilogue)
+    int flat_pitch;  // elements per image of that staging
+    FastDiv by_wo, by_w, by_upi, by_nb, by_kblocks, by_rowblocks, by_howo;
 };
 
 // 16-byte load of 8 consecutive 16-bit elements starting at element offset `off` of a tensor with
@@ -322,6 +324,17 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
                             a_dst[u][e] = (region + lds_slot(row * g.WP + col + a.pad_w)) * 16;
                         if (++col == a.W) { col = 0; ++row; }
                     }
+                }
+            }
+            if (g.flat) {
+                // where each pixel of the tile goes in the output staging (byte offset); pixels the tile does not
+                // have go to a spare image region that is never copied out
+                int* ftab = (int*)(smem + BUF0 + 2 * stage_bytes);
+                for (int f = ptid; f < PT; f += PTHREADS) {
+                    const int img = g.by_howo.div(f);
+                    const int rem = f - img * HoWo;
+                    const uint32_t sh = ((uint32_t)((n0 + img) * a.K + k0) * (uint32_t)HoWo) & 7u;
+                    ftab[f] = f < npix ? (img * g.flat_pitch + (int)sh + rem) * 2 : (g.NB * g.flat_pitch + (f & 7)) * 2;
                 }
             }
             {
@@ -789,56 +802,121 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
 
         // ---- epilogue, part 1: batch-norm / activation on the accumulators in registers, one
         //      rounding to the output type, then the tile goes into LDS as [filter][pixel].
+        // Two stagings.  Ordinarily the tile is [filter][pixel] and the store below walks along the
+        // pixel axis.  For tiles of whole images whose planes are not a multiple of 16 bytes (7x7, 14x14
+        // images) a filter row starts at any 2-byte offset of y and 8-pixel pieces straddle images; but
+        // the planes of the block's filters follow each other in y, so per image the block owns one
+        // contiguous run of y, and the tile is staged as exactly that run, shifted so that 16-byte
+        // pieces of LDS are aligned 16-byte pieces of y.  The store is then a plain copy.  Where each
+        // pixel goes comes from a table the producers wrote in the prologue.
         uint16_t* ot = (uint16_t*)(smem + BUF0);
         if (wave_on) {
-            auto stage_out = [&](auto&& act_fn) {
+            const int* ftab = (const int*)(smem + BUF0 + 2 * stage_bytes);
+            // Runs of y: a lane's four consecutive pixels stay together when the planes are multiples of
+            // 4 pixels; otherwise every pixel has its own place.
+            const bool by_pixel = g.flat == 1;
+            auto stage_out = [&](auto&& convert) __attribute__((always_inline)) {
+                if (g.flat == 0) {
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    const int kl = (wn * TN + tn) * 32 + l32;
+                    for (int tn = 0; tn < TN; ++tn) {
+                        const int kl = (wn * TN + tn) * 32 + l32;
 #pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
+                        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                            for (int q4 = 0; q4 < 4; ++q4) {
+                                uint32_t p0, p1;
+                                convert(acc[tm][tn], tn, q4, p0, p1);
+                                const int f = (tm * WM + wm) * 32 + 8 * q4 + 4 * half;
+                                *(uint2*)(ot + kl * PTP + f) = make_uint2(p0, p1);
+                            }
+                    }
+                    return;
+                }
+                int krow[TN];
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) krow[tn] = ((wn * TN + tn) * 32 + l32) * HoWo * 2;
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+                    const int f0 = (tm * WM + wm) * 32 + 4 * half;
+                    if (!by_pixel) {
+                        int fo[4];
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4) fo[q4] = ftab[f0 + 8 * q4];
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+                            for (int tn = 0; tn < TN; ++tn) {
+                                uint32_t p0, p1;
+                                convert(acc[tm][tn], tn, q4, p0, p1);
+                                *(uint2*)((unsigned char*)ot + fo[q4] + krow[tn]) = make_uint2(p0, p1);
+                            }
+                    } else {
 #pragma unroll
                         for (int q4 = 0; q4 < 4; ++q4) {
-                            float v[4];
+                            const int4 t = *(const int4*)(ftab + f0 + 8 * q4);
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) {
-                                const float t = acc[tm][tn][4 * q4 + j];
-                                v[j] = act_fn(has_bn ? fmaf(t, ca[tn].mul, ca[tn].add) : t);
+                            for (int tn = 0; tn < TN; ++tn) {
+                                uint32_t p0, p1;
+                                convert(acc[tm][tn], tn, q4, p0, p1);
+                                unsigned char* o = (unsigned char*)ot + krow[tn];
+                                *(uint16_t*)(o + t.x) = (uint16_t)p0;
+                                *(uint16_t*)(o + t.y) = (uint16_t)(p0 >> 16);
+                                *(uint16_t*)(o + t.z) = (uint16_t)p1;
+                                *(uint16_t*)(o + t.w) = (uint16_t)(p1 >> 16);
                             }
-                            const int f = (tm * WM + wm) * 32 + 8 * q4 + 4 * half;
-                            *(uint2*)(ot + kl * PTP + f) = make_uint2(pack2<DT>(v[0], v[1]), pack2<DT>(v[2], v[3]));
                         }
                     }
                 }
+            };
+            auto with_act = [&](auto&& act_fn) __attribute__((always_inline)) {
+                stage_out([&](const f32x16& t, int tn, int q4, uint32_t& p0, uint32_t& p1) __attribute__((always_inline)) {
+                    float v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) v[j] = act_fn(has_bn ? fmaf(t[4 * q4 + j], ca[tn].mul, ca[tn].add) : t[4 * q4 + j]);
+                    p0 = pack2<DT>(v[0], v[1]);
+                    p1 = pack2<DT>(v[2], v[3]);
+                });
             };
             if ((a.act == ACT_RELU || a.act == ACT_IDENTITY) && !has_bn) {
                 // the common case (the bias is already in the accumulators), kept short because only the
                 // consumer waves can do it: round, then ReLU on the packed pair, 1 instruction per value
                 const uint32_t floor2 = packed_floor(a.act == ACT_RELU);
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    const int kl = (wn * TN + tn) * 32 + l32;
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4) {
-                            const f32x16& t = acc[tm][tn];
-                            const int f = (tm * WM + wm) * 32 + 8 * q4 + 4 * half;
-                            *(uint2*)(ot + kl * PTP + f) = make_uint2(max_packed(pack2<DT>(t[4 * q4], t[4 * q4 + 1]), floor2),
-                                                                      max_packed(pack2<DT>(t[4 * q4 + 2], t[4 * q4 + 3]), floor2));
-                        }
-                    }
-                }
-            } else if (a.act == ACT_RELU) stage_out([](float t) { return fmaxf(t, 0.0f); });
-            else if (a.act == ACT_IDENTITY) stage_out([](float t) { return t; });
-            else stage_out([&](float t) { return activate(t, a.act, a.alpha); });
+                stage_out([&](const f32x16& t, int, int q4, uint32_t& p0, uint32_t& p1) __attribute__((always_inline)) {
+                    p0 = max_packed(pack2<DT>(t[4 * q4], t[4 * q4 + 1]), floor2);
+                    p1 = max_packed(pack2<DT>(t[4 * q4 + 2], t[4 * q4 + 3]), floor2);
+                });
+            } else if (a.act == ACT_RELU) with_act([](float t) { return fmaxf(t, 0.0f); });
+            else if (a.act == ACT_IDENTITY) with_act([](float t) { return t; });
+            else with_act([&](float t) { return activate(t, a.act, a.alpha); });
         }
     }
     __syncthreads();                                   // output tile complete in LDS
 
     // ---- epilogue, part 2 (all waves): the single store to device memory, 16 bytes per lane along
     //      the pixel axis.
-    {
+    if (g.flat) {
+        // the staged runs are copied out: 16 aligned bytes per lane, consecutive lanes consecutive pieces
+        const unsigned char* ot = smem + BUF0;
+        uint16_t* __restrict__ yg = (uint16_t*)a.y;
+        const int len = min(KT, k_end - k0) * HoWo;                 // elements of one image's run
+        for (int img = 0; img < nimg; ++img) {
+            const size_t e0 = ((size_t)(n0 + img) * a.K + k0) * HoWo;   // first element of the run in y
+            const int sh = (int)(e0 & 7);
+            const int nch = (len + sh + 7) >> 3;
+            uint16_t* dst0 = yg + (e0 - sh);                        // 16-byte aligned: y itself is
+            const unsigned char* src = ot + (size_t)img * g.flat_pitch * 2;
+            for (int c = tid; c < nch; c += THREADS) {
+                const u32x4 v = *(const u32x4*)(src + c * 16);
+                if (8 * c >= sh && 8 * c + 8 <= sh + len) {
+                    __builtin_nontemporal_store(v, (u32x4*)(dst0 + 8 * c));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (8 * c + e >= sh && 8 * c + e < sh + len) dst0[8 * c + e] = (uint16_t)(v[e >> 1] >> ((e & 1) * 16));
+                }
+            }
+        }
+    } else {
         const uint16_t* ot = (const uint16_t*)(smem + BUF0);
         constexpr int CH = PT / 8;                 // 8-pixel chunks per filter row
         constexpr int RSTEP = THREADS / CH;        // filter rows covered per pass
@@ -953,8 +1031,8 @@ FastDiv fast_div(int d)
 int lds_bytes(const Variant& v, const IgemmGeom& g)
 {
     const int KT = v.WN * v.TN * 32, PT = v.WM * v.TM * 32;
-    const int stages = 16 + 2 * (g.xbytes + g.wbytes);
-    const int otile = 16 + KT * (PT + 8) * 2;
+    const int stages = 16 + 2 * (g.xbytes + g.wbytes) + (g.flat ? PT * 4 : 0);   // + the table of staging offsets
+    const int otile = 16 + (g.flat ? (g.NB + 1) * g.flat_pitch * 2 : KT * (PT + 8) * 2);
     return stages > otile ? stages : otile;
 }
 
@@ -999,6 +1077,16 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     if (16 + 2 * (xb + wb) > LDS_LIMIT) return false;
     g.xbytes = (int)xb;
     g.wbytes = (int)wb;
+    {
+        // whole-image tiles with planes that are not a multiple of 16 bytes are staged as runs of y,
+        // if that staging fits where the stage buffers were (else the ordinary tile is used)
+        const int HoWo = a.Ho * a.Wo;
+        if (TH == a.Ho && (HoWo & 7) != 0) {
+            g.flat = (HoWo & 3) == 0 ? 2 : 1;
+            g.flat_pitch = (KT * HoWo + 7 + 7) & ~7;
+            if ((long long)(NB + 1) * g.flat_pitch * 2 > 2 * (xb + wb) || lds_bytes(v, g) > LDS_LIMIT) g.flat = 0;
+        }
+    }
     if (lds_bytes(v, g) > LDS_LIMIT) return false;
     if ((long long)g.row_blocks * g.img_blocks * g.k_blocks > 0x7fffffffLL) return false;
     g.by_wo = fast_div(a.Wo);
@@ -1024,6 +1112,7 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     }
     g.by_kblocks = fast_div(g.k_blocks);
     g.by_rowblocks = fast_div(g.row_blocks);
+    g.by_howo = fast_div(a.Ho * a.Wo);
     *out = g;
     return true;
 }

@@ -111,6 +111,13 @@ SMALL = [
     _v("c2", name="s1_w10_h3_pad0h", N=2, C=16, K=24, H=9, W=10, pad=(0, 1)),
     _v("c2", name="s1_w20_dilh2", N=2, C=32, K=40, H=11, W=20, pad=(2, 1), dil=(2, 1)),
     _v("c2", name="s1_w9_padh3", N=1, C=16, K=8, H=4, W=9, pad=(3, 1)),
+    # whole-image tiles staged as runs of y (planes that are not a multiple of 16 bytes): pixel-by-pixel
+    # staging (odd planes) and four-pixel staging, ragged filter blocks, a last tile with fewer images,
+    # groups (runs that start at any alignment), both 16-bit types
+    _v("c2", name="runs_5x5_k40_groups2", N=13, C=32, K=40, H=5, W=5, groups=2),
+    _v("c2", name="runs_6x6_k72", N=9, C=16, K=72, H=6, W=6),
+    _v("c2", name="runs_9x11_k33_f16", N=5, C=24, K=33, H=9, W=11, dtype=wl.F16),
+    _v("c2", name="runs_10x10_k130", N=3, C=16, K=130, H=10, W=10),
     _v("c4", name="c4_n2", N=2),
     _v("c4", name="c4_ragged", N=2, H=61, W=45, K=24),
     _v("c4", name="c4_bf16", N=1, H=64, W=64, dtype=wl.BF16),
@@ -253,6 +260,19 @@ def test_batchnorm_epilogue(base):
           rng.uniform(0.5, 2.0, w.K))
     bn = tuple(t.astype(np.float32).astype(np.float64) for t in bn)
     check_case(w, bn=bn, eps=1e-3)
+
+
+@pytest.mark.parametrize("shape", [dict(N=6, C=32, K=80, H=7, W=7), dict(N=2, C=16, K=24, H=14, W=14)], ids=["7x7", "14x14"])
+def test_every_epilogue_on_tiles_staged_as_runs(shape):
+    w = wl.small_variant(wl.WORKLOADS["c2"], **shape)
+    rng = np.random.default_rng(9)
+    bn = (rng.uniform(0.5, 1.5, w.K), rng.uniform(-0.5, 0.5, w.K), rng.uniform(-0.3, 0.3, w.K), rng.uniform(0.5, 2.0, w.K))
+    bn = tuple(t.astype(np.float32).astype(np.float64) for t in bn)
+    for act, alpha in [(cvx.CVX_ACT_IDENTITY, 0.0), (cvx.CVX_ACT_RELU, 0.0), (cvx.CVX_ACT_LEAKY_RELU, 0.1), (cvx.CVX_ACT_TANH, 0.0)]:
+        check_case(w, act=act, alpha=alpha)
+    check_case(w, bn=bn, eps=1e-3)
+    check_case(w, bn=bn, eps=1e-3, act=cvx.CVX_ACT_LOGISTIC)
+    check_case(w, use_bias=False, act=cvx.CVX_ACT_IDENTITY)
 
 
 def test_plain_conv_fwd_and_unfused_operators_agree_with_fused():
