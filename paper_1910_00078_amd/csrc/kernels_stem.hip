@@ -44,6 +44,187 @@ struct StemGeom {
 
 __device__ __forceinline__ int div_small(int n, int d, uint32_t magic) { return d == 1 ? n : (int)__umulhi((uint32_t)n, magic); }
 
+// ---- pieces both arrangements below share -------------------------------------------------------
+
+// The input patch of a tile as 16-byte loader units, XU per thread of the NT threads that load: unit
+// u of LDS row rowi = c*PH + patch row covers columns 8u - pad_w .. 8u - pad_w + 7.
+template <int XU, int NT>
+struct StemPatchLoader {
+    int dst[XU], c[XU], pr[XU], col[XU];      // LDS byte offset (-1: no unit), channel, patch row, first column
+
+    __device__ __forceinline__ void init(const ConvArgs& a, const StemGeom& g, int t)
+    {
+#pragma unroll
+        for (int j = 0; j < XU; ++j) {
+            const int ui = j * NT + t;
+            dst[j] = -1;
+            c[j] = pr[j] = col[j] = 0;
+            if (ui < g.n_units) {
+                const int rowi = div_small(ui, g.UPR, g.upr_magic);
+                const int u = ui - rowi * g.UPR;
+                c[j] = div_small(rowi, g.PH, g.ph_magic);
+                pr[j] = rowi - c[j] * g.PH;
+                col[j] = 8 * u - a.pad_w;
+                dst[j] = (rowi * g.WROW + 8 * u) * 2;
+            }
+        }
+    }
+    // Issues the loads of the patch of row block rb of image n (nothing here uses a loaded value).
+    __device__ __forceinline__ void load(const ConvArgs& a, const StemGeom& g, int n, int rb, u32x4 (&xv)[XU]) const
+    {
+        const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
+        const long long x_total = (long long)a.N * a.C * a.H * a.W;
+        const int h_lo = rb * g.TH * a.stride_h - a.pad_h;
+#pragma unroll
+        for (int j = 0; j < XU; ++j) {
+            xv[j] = u32x4{0u, 0u, 0u, 0u};
+            const int h = h_lo + pr[j];
+            if (dst[j] >= 0 && h >= 0 && h < a.H && col[j] < a.W && col[j] + 8 > 0) {
+                const long long off = ((long long)(n * a.C + c[j]) * a.H + h) * a.W + col[j];
+                if (off >= 0 && off + 8 <= x_total) {
+                    xv[j] = *(const u32x4_a2*)(xg + off);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const long long o = off + e;
+                        if (o >= 0 && o < x_total) xv[j][e >> 1] |= ((uint32_t)xg[o]) << ((e & 1) * 16);
+                    }
+                }
+            }
+        }
+    }
+    // Clears the columns outside [0, W) (they belong to a neighbouring row, or to nothing) and writes
+    // the patch into the LDS patch buffer xs.
+    __device__ __forceinline__ void store(const ConvArgs& a, unsigned char* xs, const u32x4 (&xv)[XU]) const
+    {
+#pragma unroll
+        for (int j = 0; j < XU; ++j) {
+            if (dst[j] >= 0) {
+                u32x4 v = xv[j];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int cl = col[j] + e;
+                    if (cl < 0 || cl >= a.W) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                }
+                *(u32x4*)(xs + dst[j]) = v;
+            }
+        }
+    }
+};
+
+// Filters k0 .. k0+KT-1 into LDS at ws, by NT threads (t = 0..NT-1), WU units per thread and batch: one
+// 16-byte unit per (pair = c*R + r, filter).  The S <= 8 taps of a filter row are contiguous in
+// w[k][c][r][s]; one (2-byte aligned) 16-byte load fetches them, the elements past S are cleared, and the
+// unit lands at [pair][filter].  Pairs past C*R (the odd one out) and filters past K are zero.  All loads
+// of a batch are issued before any is used.
+template <int KT, int WU, int NT>
+__device__ __forceinline__ void stem_load_filters(const ConvArgs& a, const StemGeom& g, unsigned char* ws, int k0, int t)
+{
+    const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
+    const int per_k = a.C * a.R * a.S;
+    const long long w_total = (long long)a.K * per_k;
+    const int n_wunits = 2 * g.n_ksteps * KT;
+    for (int base = 0; base < n_wunits; base += NT * WU) {
+        u32x4 wv[WU];
+#pragma unroll
+        for (int j = 0; j < WU; ++j) {
+            const int ui = base + j * NT + t;
+            wv[j] = u32x4{0u, 0u, 0u, 0u};
+            if (ui < n_wunits) {
+                const int kl = ui % KT, pair = ui / KT;
+                if (pair < g.n_pairs && k0 + kl < a.K) {
+                    const long long off = (long long)(k0 + kl) * per_k + pair * a.S;
+                    if (off + 8 <= w_total) {
+                        wv[j] = *(const u32x4_a2*)(wg + off);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            if (off + e < w_total) wv[j][e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < WU; ++j) {
+            const int ui = base + j * NT + t;
+            if (ui < n_wunits) {
+                u32x4 v = wv[j];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+                *(u32x4*)(ws + (size_t)ui * 16) = v;
+            }
+        }
+    }
+}
+
+// Byte offset, inside a patch buffer, of the (channel, filter row) pair that half-wave `half` multiplies in
+// each of the NKS k-steps (0 for the odd pair out, whose weights are zero).
+template <int NKS>
+__device__ __forceinline__ void stem_row_offsets(const ConvArgs& a, const StemGeom& g, int half, int (&rowoff)[NKS])
+{
+    int c = 0, r = half;
+    while (r >= a.R) { r -= a.R; ++c; }
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+        rowoff[ks] = (2 * ks + half) < g.n_pairs ? ((c * g.PH + r) * g.WROW) * 2 : 0;
+        r += 2;
+        while (r >= a.R) { r -= a.R; ++c; }
+    }
+}
+
+// The reduction with a compile-time number of k-steps, straight-line and in a pinned order: one k-step
+// = two (channel, filter row) pairs, one per half-wave; after each MFMA of step ks one fragment of step
+// ks+1 is read (pixels 0, the filters, then the other pixels: the order the next step's MFMAs want
+// them), so the waits the compiler inserts are partial and the LDS latency hides behind the matrix pipe.
+// xs: patch buffer; wl: this lane's position in the filter region; xbase: the lane's pixel operands.
+template <int DT, int TM, int TN, int NKS, int KT>
+__device__ __forceinline__ void stem_multiply(const unsigned char* xs, const unsigned char* wl, const int (&xbase)[TM],
+                                              const int (&rowoff)[NKS], f32x16 (&acc)[TM][TN])
+{
+    u32x4 fa[2][TM], fb[2][TN];
+    auto read_a = [&](int tm, int ks) __attribute__((always_inline)) {
+        const uint32_t* p = (const uint32_t*)(xs + xbase[tm] + rowoff[ks]);   // 4-byte aligned
+        return u32x4{p[0], p[1], p[2], p[3]};
+    };
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(wl + tn * 32 * 16);
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) fa[0][tm] = read_a(tm, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+        const int b = ks & 1, nb = b ^ 1;
+        const bool more_k = ks + 1 < NKS;
+        int issued = 0;
+        auto read_next = [&]() __attribute__((always_inline)) {
+            if (issued == 0) fa[nb][0] = read_a(0, ks + 1);
+            else if (issued <= TN) fb[nb][issued - 1] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + (issued - 1) * 32) * 16);
+            else fa[nb][issued - TN] = read_a(issued - TN, ks + 1);
+            ++issued;
+        };
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (more_k && issued < TM + TN) {
+                    read_next();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < TM + TN; ++j) {
+            if (more_k && issued < TM + TN) {
+                read_next();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+}
+
 // Block: 4 waves, PT = 4*TM*32 pixels (TH full output rows) x KT = TN*32 filters.  Blocks are
 // persistent: block b works through tiles b, b + gridDim.x, ... with the filters resident in LDS and
 // the loop software-pipelined -- the input patch of the next tile is fetched into registers while the
@@ -68,9 +249,6 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int HoWo = a.Ho * a.Wo;
-    const long long x_total = (long long)a.N * a.C * a.H * a.W;
-    const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
-    const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
     uint16_t* __restrict__ yg = (uint16_t*)a.y;
 
     unsigned char* ws = smem;                            // filters
@@ -81,22 +259,8 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
     const int n_tiles = tiles_per_kb * g.k_blocks;
 
     // ---- tile-independent bookkeeping
-    // input loader units: unit u of LDS row rowi = c*PH + patch row covers columns 8u - pad_w .. +7
-    int x_dst[XU], x_c[XU], x_pr[XU], x_col[XU];
-#pragma unroll
-    for (int j = 0; j < XU; ++j) {
-        const int ui = j * THREADS + tid;
-        x_dst[j] = -1;
-        x_c[j] = x_pr[j] = x_col[j] = 0;
-        if (ui < g.n_units) {
-            const int rowi = div_small(ui, g.UPR, g.upr_magic);
-            const int u = ui - rowi * g.UPR;
-            x_c[j] = div_small(rowi, g.PH, g.ph_magic);
-            x_pr[j] = rowi - x_c[j] * g.PH;
-            x_col[j] = 8 * u - a.pad_w;
-            x_dst[j] = (rowi * g.WROW + 8 * u) * 2;
-        }
-    }
+    StemPatchLoader<XU, THREADS> patch;
+    patch.init(a, g, tid);
     // operand addresses: byte offset of (patch row py*stride_h, column index px*stride_w) per pixel tile
     int xbase[TM];
 #pragma unroll
@@ -110,99 +274,13 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
     // With a compile-time number of k-steps (NKS > 0) the byte offset of every step's (channel, filter
     // row) pair is worked out once; the reduction loop is then straight-line code.
     int rowoff[NKS > 0 ? NKS : 1];
-    if constexpr (NKS > 0) {
-        int c = 0, r = half;
-        while (r >= a.R) { r -= a.R; ++c; }
-#pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) {
-            rowoff[ks] = (2 * ks + half) < g.n_pairs ? ((c * g.PH + r) * g.WROW) * 2 : 0;
-            r += 2;
-            while (r >= a.R) { r -= a.R; ++c; }
-        }
-    }
+    if constexpr (NKS > 0) stem_row_offsets<NKS>(a, g, half, rowoff);
 
-    // Issues the loads of one tile's input patch (nothing here uses a loaded value).
     auto load_patch = [&](int tile, u32x4 (&xv)[XU]) __attribute__((always_inline)) {
         const int pt = tile % tiles_per_kb;
         const int n = pt / g.row_blocks;
-        const int rb = pt - n * g.row_blocks;
-        const int h_lo = rb * g.TH * a.stride_h - a.pad_h;
-#pragma unroll
-        for (int j = 0; j < XU; ++j) {
-            xv[j] = u32x4{0u, 0u, 0u, 0u};
-            const int h = h_lo + x_pr[j];
-            if (x_dst[j] >= 0 && h >= 0 && h < a.H && x_col[j] < a.W && x_col[j] + 8 > 0) {
-                const long long off = ((long long)(n * a.C + x_c[j]) * a.H + h) * a.W + x_col[j];
-                if (off >= 0 && off + 8 <= x_total) {
-                    xv[j] = *(const u32x4_a2*)(xg + off);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const long long o = off + e;
-                        if (o >= 0 && o < x_total) xv[j][e >> 1] |= ((uint32_t)xg[o]) << ((e & 1) * 16);
-                    }
-                }
-            }
-        }
+        patch.load(a, g, n, pt - n * g.row_blocks, xv);
     };
-    // Clears the columns outside [0, W) (they belong to a neighbouring row, or to nothing) and writes
-    // the patch into LDS.
-    auto store_patch = [&](const u32x4 (&xv)[XU]) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < XU; ++j) {
-            if (x_dst[j] >= 0) {
-                u32x4 v = xv[j];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int col = x_col[j] + e;
-                    if (col < 0 || col >= a.W) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                }
-                *(u32x4*)(xs + x_dst[j]) = v;
-            }
-        }
-    };
-    // Filters of filter block kb: one 16-byte unit per (pair = c*R + r, filter): the S <= 8 taps of a
-    // filter row are contiguous in w[k][c][r][s]; one (2-byte aligned) 16-byte load fetches them, the
-    // elements past S are cleared, and the unit lands at [pair][filter].  Pairs past C*R (the odd one
-    // out) and filters past K are zero.  All loads of a batch are issued before any is used.
-    auto load_filters = [&](int k0) __attribute__((always_inline)) {
-        const int per_k = a.C * a.R * a.S;
-        const long long w_total = (long long)a.K * per_k;
-        const int n_wunits = 2 * g.n_ksteps * KT;
-        for (int base = 0; base < n_wunits; base += THREADS * WU) {
-            u32x4 wv[WU];
-#pragma unroll
-            for (int j = 0; j < WU; ++j) {
-                const int ui = base + j * THREADS + tid;
-                wv[j] = u32x4{0u, 0u, 0u, 0u};
-                if (ui < n_wunits) {
-                    const int kl = ui % KT, pair = ui / KT;
-                    if (pair < g.n_pairs && k0 + kl < a.K) {
-                        const long long off = (long long)(k0 + kl) * per_k + pair * a.S;
-                        if (off + 8 <= w_total) {
-                            wv[j] = *(const u32x4_a2*)(wg + off);
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e)
-                                if (off + e < w_total) wv[j][e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
-                        }
-                    }
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < WU; ++j) {
-                const int ui = base + j * THREADS + tid;
-                if (ui < n_wunits) {
-                    u32x4 v = wv[j];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                    *(u32x4*)(ws + (size_t)ui * 16) = v;
-                }
-            }
-        }
-    };
-
     int tile = blockIdx.x;
     if (tile >= n_tiles) return;
     int cur_kb = -1;
@@ -212,10 +290,10 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
     // Brings a tile's patch (already in xv) into LDS, and the filters and epilogue constants if the
     // filter block changed (once per block unless K > KT).
     auto enter_tile = [&](int tl) __attribute__((always_inline)) {
-        store_patch(xv);
+        patch.store(a, xs, xv);
         const int kb = tl / tiles_per_kb;
         if (kb != cur_kb) {
-            load_filters(kb * KT);
+            stem_load_filters<KT, WU, THREADS>(a, g, ws, kb * KT, tid);
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(kb * KT + tn * 32 + l32, a.K - 1));
             cur_kb = kb;
@@ -261,52 +339,7 @@ __global__ void __launch_bounds__(256) stem_kernel(ConvArgs a, StemGeom g)
             }
         if (wave_on) {
             if constexpr (NKS > 0) {
-                // Straight-line, pinned order: after each MFMA of step ks one fragment of step ks+1 is
-                // read (filters first), so the waits the compiler inserts are partial and the LDS
-                // latency hides behind the matrix pipe.
-                const unsigned char* wl = ws + (size_t)(half * KT + l32) * 16;
-                u32x4 fa[2][TM], fb[2][TN];
-                auto read_a = [&](int tm, int ks) __attribute__((always_inline)) {
-                    const uint32_t* p = (const uint32_t*)(xs + xbase[tm] + rowoff[ks]);   // 4-byte aligned
-                    return u32x4{p[0], p[1], p[2], p[3]};
-                };
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(wl + tn * 32 * 16);
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) fa[0][tm] = read_a(tm, 0);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) {
-                    const int b = ks & 1, nb = b ^ 1;
-                    const bool more_k = ks + 1 < NKS;
-                    int issued = 0;
-                    auto read_next = [&]() __attribute__((always_inline)) {
-                        // in the order the next step's MFMAs want them: pixels 0, the filters, then the other pixels
-                        if (issued == 0) fa[nb][0] = read_a(0, ks + 1);
-                        else if (issued <= TN) fb[nb][issued - 1] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + (issued - 1) * 32) * 16);
-                        else fa[nb][issued - TN] = read_a(issued - TN, ks + 1);
-                        ++issued;
-                    };
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) {
-                            acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (more_k && issued < TM + TN) {
-                                read_next();
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
-                        }
-                    }
-#pragma unroll
-                    for (int j = 0; j < TM + TN; ++j) {
-                        if (more_k && issued < TM + TN) {
-                            read_next();
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
-                }
+                stem_multiply<DT, TM, TN, NKS, KT>(xs, ws + (size_t)(half * KT + l32) * 16, xbase, rowoff, acc);
             } else {
             int pr = half;                               // this half-wave's pair index
             int c = 0, r = half;
@@ -462,8 +495,6 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int HoWo = a.Ho * a.Wo;
-    const uint16_t* __restrict__ xg = (const uint16_t*)a.x;
-    const uint16_t* __restrict__ wg = (const uint16_t*)a.w;
 
     unsigned char* ws = smem;                                        // filters [pair][KT] x 16 bytes
     unsigned char* xs0 = smem + g.wbytes;                            // two patch buffers
@@ -478,65 +509,15 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
         // loader waves
         // =========================================================================================
         const int lt = tid - NCW * 64;
-        const long long x_total = (long long)a.N * a.C * a.H * a.W;
-        // unit u of LDS row rowi = c*PH + patch row covers columns 8u - pad_w .. +7
-        int x_dst[XU], x_c[XU], x_pr[XU], x_col[XU];
-#pragma unroll
-        for (int j = 0; j < XU; ++j) {
-            const int ui = j * LTHREADS + lt;
-            x_dst[j] = -1;
-            x_c[j] = x_pr[j] = x_col[j] = 0;
-            if (ui < g.n_units) {
-                const int rowi = div_small(ui, g.UPR, g.upr_magic);
-                const int u = ui - rowi * g.UPR;
-                x_c[j] = div_small(rowi, g.PH, g.ph_magic);
-                x_pr[j] = rowi - x_c[j] * g.PH;
-                x_col[j] = 8 * u - a.pad_w;
-                x_dst[j] = (rowi * g.WROW + 8 * u) * 2;
-            }
-        }
+        StemPatchLoader<XU, LTHREADS> patch;
+        patch.init(a, g, lt);
         u32x4 xv[XU];
-        // issues the loads of one tile's input patch (nothing here uses a loaded value)
         auto load_patch = [&](int i) __attribute__((always_inline)) {
             const int tile = (int)blockIdx.x + i * (int)gridDim.x;
             const int n = tile / g.row_blocks;
-            const int rb = tile - n * g.row_blocks;
-            const int h_lo = rb * g.TH * a.stride_h - a.pad_h;
-#pragma unroll
-            for (int j = 0; j < XU; ++j) {
-                xv[j] = u32x4{0u, 0u, 0u, 0u};
-                const int h = h_lo + x_pr[j];
-                if (x_dst[j] >= 0 && h >= 0 && h < a.H && x_col[j] < a.W && x_col[j] + 8 > 0) {
-                    const long long off = ((long long)(n * a.C + x_c[j]) * a.H + h) * a.W + x_col[j];
-                    if (off >= 0 && off + 8 <= x_total) {
-                        xv[j] = *(const u32x4_a2*)(xg + off);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const long long o = off + e;
-                            if (o >= 0 && o < x_total) xv[j][e >> 1] |= ((uint32_t)xg[o]) << ((e & 1) * 16);
-                        }
-                    }
-                }
-            }
+            patch.load(a, g, n, tile - n * g.row_blocks, xv);
         };
-        // clears the columns outside [0, W) (they belong to a neighbouring row, or to nothing) and
-        // writes the patch into patch buffer `buf`
-        auto store_patch = [&](int buf) __attribute__((always_inline)) {
-            unsigned char* xs = xs0 + buf * g.xbytes;
-#pragma unroll
-            for (int j = 0; j < XU; ++j) {
-                if (x_dst[j] >= 0) {
-                    u32x4 v = xv[j];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int col = x_col[j] + e;
-                        if (col < 0 || col >= a.W) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                    }
-                    *(u32x4*)(xs + x_dst[j]) = v;
-                }
-            }
-        };
+        auto store_patch = [&](int buf) __attribute__((always_inline)) { patch.store(a, xs0 + buf * g.xbytes, xv); };
         load_patch(0);
         store_patch(0);
         bar();                                                       // filters and the first patch are in LDS
@@ -565,56 +546,9 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
             xbase[tm] = f < g.TH * a.Wo ? ((py * a.stride_h) * g.WROW + px * a.stride_w) * 2 : 0;
         }
         int rowoff[NKS];
-        {
-            int c = 0, r = half;
-            while (r >= a.R) { r -= a.R; ++c; }
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                rowoff[ks] = (2 * ks + half) < g.n_pairs ? ((c * g.PH + r) * g.WROW) * 2 : 0;
-                r += 2;
-                while (r >= a.R) { r -= a.R; ++c; }
-            }
-        }
-        // ---- filters, once per block, by the multiply waves (the loaders are already fetching the first
-        //      patch): one 16-byte unit per (pair = c*R + r, filter); the S <= 8 taps of a filter row are contiguous in w[k][c][r][s]; elements past S are cleared;
-        //      pairs past C*R (the odd one out) and filters past K are zero.
-        {
-            const int per_k = a.C * a.R * a.S;
-            const long long w_total = (long long)a.K * per_k;
-            const int n_wunits = 2 * g.n_ksteps * KT;
-            for (int base = 0; base < n_wunits; base += NCW * 64 * WU) {
-                u32x4 wv[WU];
-#pragma unroll
-                for (int j = 0; j < WU; ++j) {
-                    const int ui = base + j * (NCW * 64) + tid;
-                    wv[j] = u32x4{0u, 0u, 0u, 0u};
-                    if (ui < n_wunits) {
-                        const int kl = ui % KT, pair = ui / KT;
-                        if (pair < g.n_pairs && kl < a.K) {
-                            const long long off = (long long)kl * per_k + pair * a.S;
-                            if (off + 8 <= w_total) {
-                                wv[j] = *(const u32x4_a2*)(wg + off);
-                            } else {
-#pragma unroll
-                                for (int e = 0; e < 8; ++e)
-                                    if (off + e < w_total) wv[j][e >> 1] |= ((uint32_t)wg[off + e]) << ((e & 1) * 16);
-                            }
-                        }
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < WU; ++j) {
-                    const int ui = base + j * (NCW * 64) + tid;
-                    if (ui < n_wunits) {
-                        u32x4 v = wv[j];
-#pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            if (e >= a.S) v[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-                        *(u32x4*)(ws + (size_t)ui * 16) = v;
-                    }
-                }
-            }
-        }
+        stem_row_offsets<NKS>(a, g, half, rowoff);
+        // filters, once per block, by the multiply waves (the loaders are already fetching the first patch)
+        stem_load_filters<KT, WU, NCW * 64>(a, g, ws, 0, tid);
         ChannelAffine ca[TN];
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) ca[tn] = channel_affine<DT>(a, min(tn * 32 + l32, a.K - 1));
@@ -648,50 +582,7 @@ __global__ void __launch_bounds__(STREAM_THREADS) stem_stream_kernel(ConvArgs a,
                     for (int r = 0; r < 16; ++r) acc[tm][tn][r] = seed;
                 }
             if (wave_on) {
-                // straight-line, pinned order: after each MFMA of step ks one fragment of step ks+1 is
-                // read (filters first), so the LDS latency hides behind the matrix pipe
-                u32x4 fa[2][TM], fb[2][TN];
-                auto read_a = [&](int tm, int ks) __attribute__((always_inline)) {
-                    const uint32_t* p = (const uint32_t*)(xs + xbase[tm] + rowoff[ks]);   // 4-byte aligned
-                    return u32x4{p[0], p[1], p[2], p[3]};
-                };
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) fb[0][tn] = *(const u32x4*)(wl + tn * 32 * 16);
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) fa[0][tm] = read_a(tm, 0);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) {
-                    const int b = ks & 1, nb = b ^ 1;
-                    const bool more_k = ks + 1 < NKS;
-                    int issued = 0;
-                    auto read_next = [&]() __attribute__((always_inline)) {
-                        // in the order the next step's MFMAs want them: pixels 0, the filters, then the other pixels
-                        if (issued == 0) fa[nb][0] = read_a(0, ks + 1);
-                        else if (issued <= TN) fb[nb][issued - 1] = *(const u32x4*)(wl + ((ks + 1) * 2 * KT + (issued - 1) * 32) * 16);
-                        else fa[nb][issued - TN] = read_a(issued - TN, ks + 1);
-                        ++issued;
-                    };
-#pragma unroll
-                    for (int tm = 0; tm < TM; ++tm) {
-#pragma unroll
-                        for (int tn = 0; tn < TN; ++tn) {
-                            acc[tm][tn] = mfma_32x32x16<DT>(fa[b][tm], fb[b][tn], acc[tm][tn]);
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (more_k && issued < TM + TN) {
-                                read_next();
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
-                        }
-                    }
-#pragma unroll
-                    for (int j = 0; j < TM + TN; ++j) {
-                        if (more_k && issued < TM + TN) {
-                            read_next();
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
-                }
+                stem_multiply<DT, TM, TN, NKS, KT>(xs, wl, xbase, rowoff, acc);
 
                 // epilogue: 32 filters at a time through the wave's own patch, then 16 bytes per lane
                 // along the pixel axis (the tile is TH whole output rows: its pixels are contiguous in y)
