@@ -49,14 +49,16 @@ struct IgemmGeom {
     int PSLOTS;      // physical ones: one spare 16-byte slot after every 8 (see lds_slot)
     int row_blocks, img_blocks, k_blocks;   // k_blocks counts the filter blocks of all groups
     int cg, kg, kb_per_group;              // channels and filters per group (Sec. IV-A grouped convolution); filter blocks per group
-    int xcd_kparts;  // the 8 XCDs split the tile grid into (8 / xcd_kparts) pixel-block ranges x xcd_kparts filter-block ranges
+    int xcd_kparts;  // the 8 XCDs split the tile grid into (8 / xcd_kparts) pixel-block ranges x xcd_kparts filter-block ranges; 0: plain order
+    int xcd_kshift;  // log2(xcd_kparts)
+    int xcd_ppx;     // pixel blocks per XCD (filter blocks per XCD: by_kpx.d)
     int n_stages;    // ceil(C / CC)
     int a_units;     // input loader units per stage
     int b_units;     // filter loader units per stage (register-transposed path)
     int xbytes, wbytes;   // LDS bytes per stage for input and filters
     int flat;        // output staging: 0 = [filter][pixel] tile; 1, 2 = the tile's run of y, image by image (see the epilogue)
     int flat_pitch;  // elements per image of that staging
-    FastDiv by_wo, by_w, by_upi, by_nb, by_kblocks, by_rowblocks, by_howo;
+    FastDiv by_wo, by_w, by_upi, by_nb, by_kblocks, by_rowblocks, by_howo, by_kpx;
 };
 
 // 16-byte load of 8 consecutive 16-bit elements starting at element offset `off` of a tensor with
@@ -160,23 +162,21 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
     //      and the filters of its filter blocks once.  Inside the rectangle, blocks that share an input
     //      tile (differing only in the filter block) are neighbours.
     int pb, kb;
-    {
-        const int nblk = gridDim.x, kblocks = (int)g.by_kblocks.d;
-        if ((nblk & 7) == 0) {
-            const int x = blockIdx.x & 7, j = blockIdx.x >> 3;     // XCD, index inside it
-            const int kparts = g.xcd_kparts, pparts = 8 / kparts;
-            const int kpx = kblocks / kparts;                          // filter blocks per XCD
-            const int ppx = (nblk / kblocks) / pparts;                 // pixel blocks per XCD
-            const int pbl = kpx == 1 ? j : j / kpx;
-            pb = (x / kparts) * ppx + pbl;
-            kb = (x % kparts) * kpx + (j - pbl * kpx);
-        } else {
-            pb = kblocks == 1 ? (int)blockIdx.x : (int)blockIdx.x / kblocks;
-            kb = (int)blockIdx.x - pb * kblocks;
-        }
+    if (g.xcd_kparts > 0) {
+        // the division constants of the rectangle come from the host: this decode is on the way to the
+        // first load of every block
+        const int x = blockIdx.x & 7, j = blockIdx.x >> 3;         // XCD, index inside it
+        const int pbl = g.by_kpx.div(j);                           // j < 65536 here (host)
+        pb = (x >> g.xcd_kshift) * g.xcd_ppx + pbl;
+        kb = (x & (g.xcd_kparts - 1)) * (int)g.by_kpx.d + (j - pbl * (int)g.by_kpx.d);
+    } else {
+        const int kblocks = (int)g.by_kblocks.d;
+        pb = kblocks == 1 ? (int)blockIdx.x : (int)blockIdx.x / kblocks;
+        kb = (int)blockIdx.x - pb * kblocks;
     }
-    const int ib = g.by_rowblocks.d == 1u ? pb : pb / (int)g.by_rowblocks.d;
-    const int rb = pb - ib * (int)g.by_rowblocks.d;
+    const int rowblocks = (int)g.by_rowblocks.d;
+    const int ib = rowblocks == 1 ? pb : (pb < 65536 ? g.by_rowblocks.div(pb) : pb / rowblocks);
+    const int rb = pb - ib * rowblocks;
     // grouped convolution: filter block kb belongs to group grp, which reads input channels
     // [c_first, c_first + cg) and owns filters [k0 .. k_end)
     const int grp = g.kb_per_group == g.k_blocks ? 0 : kb / g.kb_per_group;
@@ -1095,18 +1095,22 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, IgemmGeom* out)
     g.by_nb = fast_div(g.NB);
     // XCD rectangles: p pixel-block ranges x k filter-block ranges, p * k = 8; the chip then fetches about
     // k * input + p * filters bytes (each XCD its ranges once)
-    g.xcd_kparts = 1;
+    g.xcd_kparts = 0;
     {
-        const long long pblocks = (long long)g.row_blocks * g.img_blocks;
+        const long long pblocks = (long long)g.row_blocks * g.img_blocks, nblk = pblocks * g.k_blocks;
         const double in_bytes = 2.0 * a.N * a.C * a.H * a.W, w_bytes = 2.0 * a.K * g.cg * taps;
         double best = 1e300;
-        for (int k = 1; k <= 8; k *= 2) {
+        // (the in-kernel decode divides the index inside an XCD with a 16-bit magic number)
+        for (int k = 1, sh = 0; k <= 8 && (nblk & 7) == 0 && (nblk >> 3) < 65536; k *= 2, ++sh) {
             const int pp = 8 / k;
             if (g.k_blocks % k || pblocks % pp) continue;
             const double fetched = k * in_bytes + pp * w_bytes;
             if (fetched < best) {
                 best = fetched;
                 g.xcd_kparts = k;
+                g.xcd_kshift = sh;
+                g.xcd_ppx = (int)(pblocks / pp);
+                g.by_kpx = fast_div(g.k_blocks / k);
             }
         }
     }
