@@ -32,17 +32,24 @@ struct Geom {
     int x_elems, w_elems;        // floats staged per chunk: CC * NB * PH * W and KT * CC * taps
     int wpitch;                  // floats per filter row in LDS: CC * taps, made odd
     int xfloats, wfloats;        // LDS floats per buffer for input and filters
+    int xorg;                    // LDS rows start with xorg unused floats, so that image column 0 sits on a 16-byte boundary (vector staging)
+    int x_units, w_units;        // 16-byte pieces staged per chunk (vector staging)
+    int vec;                     // 1: the vector-staging kernel runs
 };
 
 
 constexpr int THREADS = 256;
 constexpr int XE = 16;           // input elements a thread stages per chunk, at most
 constexpr int WE = 24;           // filter elements a thread stages per chunk, at most
+constexpr int XV = 4, WV = 6;    // the same in 16-byte pieces (vector staging)
 
 // WM x WN waves, each TM x TN tiles of 32 pixels x 32 filters; CC channels per chunk; TAPS = R * S
 // compiled in (the multiply loop is then fully unrolled, with the next step's fragments read while the
 // current step multiplies), or 0 for any filter size.
-template <int WM, int WN, int TM, int TN, int CC, int TAPS>
+// VEC: the chunk is staged in 16-byte pieces (image rows and filter rows that are multiples of four floats on
+// 16-byte boundaries, whole channel chunks): a quarter of the load and LDS-write instructions and half the
+// registers of the element-wise staging, which serves every other shape.
+template <int WM, int WN, int TM, int TN, int CC, int TAPS, bool VEC>
 __global__ void __launch_bounds__(THREADS) tiled_f32_kernel(ConvArgs a, Geom g)
 {
     static_assert(WM * WN * 64 == THREADS && CC % 2 == 0 && CC <= 16 && XE <= 16 && WE <= 32, "four waves, channel pairs, 4-bit channel indices");
@@ -75,9 +82,13 @@ __global__ void __launch_bounds__(THREADS) tiled_f32_kernel(ConvArgs a, Geom g)
     const int buf_floats = g.xfloats + g.wfloats;
 
     // ---- what this thread stages per chunk: fixed positions, only the channel base moves
-    int x_src[XE], x_dst[XE];                          // global offset inside a channel chunk (-1: zero), LDS float offset (-1: none)
+    constexpr int NXE = VEC ? 1 : XE, NWE = VEC ? 1 : WE, NXV = VEC ? XV : 1, NWV = VEC ? WV : 1;
+    int x_src[NXE], x_dst[NXE];                        // global offset inside a channel chunk (-1: zero), LDS float offset (-1: none)
     unsigned long long x_ch = 0ull;                    // 4 bits per element: its channel inside the chunk
-    {
+    int w_src[NWE], w_dst[NWE];
+    unsigned long long w_ch[2] = {0ull, 0ull};
+    int xv_src[NXV], xv_dst[NXV], wv_src[NWV], wv_dst[NWV];   // vector staging: -1 = nothing to fetch (LDS keeps its zeros)
+    if constexpr (!VEC) {
         const int per_c = g.NB * g.PH * a.W;
 #pragma unroll
         for (int i = 0; i < XE; ++i) {
@@ -94,10 +105,6 @@ __global__ void __launch_bounds__(THREADS) tiled_f32_kernel(ConvArgs a, Geom g)
                 if (img < nimg && h >= 0 && h < a.H) x_src[i] = ((img * a.C + c) * a.H + h) * a.W + col;
             }
         }
-    }
-    int w_src[WE], w_dst[WE];
-    unsigned long long w_ch[2] = {0ull, 0ull};
-    {
         const int per_k = CC * taps;
 #pragma unroll
         for (int i = 0; i < WE; ++i) {
@@ -111,35 +118,97 @@ __global__ void __launch_bounds__(THREADS) tiled_f32_kernel(ConvArgs a, Geom g)
                 if (k0 + k < k_end) w_src[i] = k * g.cg * taps + j;      // j = c * taps + tap, contiguous in memory
             }
         }
+    } else {
+        const int w4 = a.W >> 2, per_c = g.NB * g.PH * w4;
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            const int u = tid + i * THREADS;
+            xv_src[i] = xv_dst[i] = -1;
+            if (u < g.x_units) {
+                const int c = u / per_c, r1 = u - c * per_c;
+                const int img = r1 / (g.PH * w4), r2 = r1 - img * (g.PH * w4);
+                const int row = r2 / w4, col = 4 * (r2 - row * w4);
+                const int h = h_lo + row;
+                if (img < nimg && h >= 0 && h < a.H) {
+                    xv_src[i] = ((img * a.C + c) * a.H + h) * a.W + col;
+                    xv_dst[i] = c * g.plane + (img * g.PH + row) * g.WP + g.xorg + a.pad_w + col;
+                }
+            }
+        }
+        const int per_k = (CC * taps) >> 2;
+#pragma unroll
+        for (int i = 0; i < WV; ++i) {
+            const int u = tid + i * THREADS;
+            wv_src[i] = wv_dst[i] = -1;
+            if (u < g.w_units) {
+                const int k = u / per_k, j = 4 * (u - k * per_k);
+                if (k0 + k < k_end) {
+                    wv_src[i] = k * g.cg * taps + j;
+                    wv_dst[i] = k * g.wpitch + j;
+                }
+            }
+        }
     }
     const size_t x_base = ((size_t)n0 * a.C + c_first) * HW;
     const size_t w_base = (size_t)k0 * g.cg * taps;
 
-    float xr[XE], wr[WE];
+    float xr[NXE], wr[NWE];
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef float f32x2v __attribute__((ext_vector_type(2)));
+    f32x4 xr4[NXV], wr4[NWV];
     auto load_chunk = [&](int st) {
         const int c0 = st * CC;
+        if constexpr (!VEC) {
 #pragma unroll
-        for (int i = 0; i < XE; ++i) {
-            float v = 0.0f;
-            if (x_src[i] >= 0 && c0 + (int)((x_ch >> (4 * i)) & 15ull) < g.cg) v = xg[x_base + (size_t)c0 * HW + x_src[i]];
-            xr[i] = v;
-        }
+            for (int i = 0; i < XE; ++i) {
+                float v = 0.0f;
+                if (x_src[i] >= 0 && c0 + (int)((x_ch >> (4 * i)) & 15ull) < g.cg) v = xg[x_base + (size_t)c0 * HW + x_src[i]];
+                xr[i] = v;
+            }
 #pragma unroll
-        for (int i = 0; i < WE; ++i) {
-            float v = 0.0f;
-            if (w_src[i] >= 0 && c0 + (int)((w_ch[i >> 4] >> (4 * (i & 15))) & 15ull) < g.cg) v = wg[w_base + (size_t)c0 * taps + w_src[i]];
-            wr[i] = v;
+            for (int i = 0; i < WE; ++i) {
+                float v = 0.0f;
+                if (w_src[i] >= 0 && c0 + (int)((w_ch[i >> 4] >> (4 * (i & 15))) & 15ull) < g.cg) v = wg[w_base + (size_t)c0 * taps + w_src[i]];
+                wr[i] = v;
+            }
+        } else {
+            const float* xc = xg + x_base + (size_t)c0 * HW;
+            const float* wc = wg + w_base + (size_t)c0 * taps;
+#pragma unroll
+            for (int i = 0; i < XV; ++i) {
+                f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (xv_src[i] >= 0) v = *(const f32x4*)(xc + xv_src[i]);
+                xr4[i] = v;
+            }
+#pragma unroll
+            for (int i = 0; i < WV; ++i) {
+                f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (wv_src[i] >= 0) v = *(const f32x4*)(wc + wv_src[i]);
+                wr4[i] = v;
+            }
         }
     };
     auto store_chunk = [&](int buf) {
         float* xs = lds + buf * buf_floats;
         float* ws = xs + g.xfloats;
+        if constexpr (!VEC) {
 #pragma unroll
-        for (int i = 0; i < XE; ++i)
-            if (x_dst[i] >= 0) xs[x_dst[i]] = xr[i];
+            for (int i = 0; i < XE; ++i)
+                if (x_dst[i] >= 0) xs[x_dst[i]] = xr[i];
 #pragma unroll
-        for (int i = 0; i < WE; ++i)
-            if (w_dst[i] >= 0) ws[w_dst[i]] = wr[i];
+            for (int i = 0; i < WE; ++i)
+                if (w_dst[i] >= 0) ws[w_dst[i]] = wr[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < XV; ++i)
+                if (xv_dst[i] >= 0) *(f32x4*)(xs + xv_dst[i]) = xr4[i];
+#pragma unroll
+            for (int i = 0; i < WV; ++i)
+                if (wv_dst[i] >= 0) {                              // filter rows are 8-byte, not 16-byte aligned in LDS
+                    *(f32x2v*)(ws + wv_dst[i]) = f32x2v{wr4[i][0], wr4[i][1]};
+                    *(f32x2v*)(ws + wv_dst[i] + 2) = f32x2v{wr4[i][2], wr4[i][3]};
+                }
+        }
     };
 
     // ---- fragment addresses: pixel operand per tile (float offset of the tile's pixel at tap (0,0),
@@ -154,7 +223,7 @@ __global__ void __launch_bounds__(THREADS) tiled_f32_kernel(ConvArgs a, Geom g)
             rem = f - img * ppi;
         }
         const int py = rem / a.Wo, px = rem - py * a.Wo;
-        xo[tm] = f < npix ? ((img * g.PH + py * a.stride_h) * g.WP + px * a.stride_w) + half * g.plane : half * g.plane;
+        xo[tm] = g.xorg + (f < npix ? ((img * g.PH + py * a.stride_h) * g.WP + px * a.stride_w) + half * g.plane : half * g.plane);
     }
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) wo[tn] = g.xfloats + ((wn * TN + tn) * 32 + l32) * g.wpitch + half * taps;
@@ -273,22 +342,23 @@ struct Variant {
     const char* name;
     int WM, WN, TM, TN, CC, TAPS;
     void (*kern)(ConvArgs, Geom);
+    void (*kern_vec)(ConvArgs, Geom);      // vector staging, or null
 };
 
 // name: tiled_f32_<pixels per block>x<filters per block>_c<channels per chunk>[_<filter size>]
 const Variant kVariants[] = {
-    {"tiled_f32_256x64_c8_3x3", 4, 1, 2, 2, 8, 9, tiled_f32_kernel<4, 1, 2, 2, 8, 9>},
-    {"tiled_f32_128x64_c8_3x3", 4, 1, 1, 2, 8, 9, tiled_f32_kernel<4, 1, 1, 2, 8, 9>},
-    {"tiled_f32_256x64_c16_1x1", 4, 1, 2, 2, 16, 1, tiled_f32_kernel<4, 1, 2, 2, 16, 1>},
-    {"tiled_f32_256x64_c8", 4, 1, 2, 2, 8, 0, tiled_f32_kernel<4, 1, 2, 2, 8, 0>},
-    {"tiled_f32_128x64_c8", 4, 1, 1, 2, 8, 0, tiled_f32_kernel<4, 1, 1, 2, 8, 0>},
-    {"tiled_f32_128x32_c8", 4, 1, 1, 1, 8, 0, tiled_f32_kernel<4, 1, 1, 1, 8, 0>},
-    {"tiled_f32_128x32_c2", 4, 1, 1, 1, 2, 0, tiled_f32_kernel<4, 1, 1, 1, 2, 0>},
+    {"tiled_f32_256x64_c8_3x3", 4, 1, 2, 2, 8, 9, tiled_f32_kernel<4, 1, 2, 2, 8, 9, false>, tiled_f32_kernel<4, 1, 2, 2, 8, 9, true>},
+    {"tiled_f32_128x64_c8_3x3", 4, 1, 1, 2, 8, 9, tiled_f32_kernel<4, 1, 1, 2, 8, 9, false>, tiled_f32_kernel<4, 1, 1, 2, 8, 9, true>},
+    {"tiled_f32_256x64_c16_1x1", 4, 1, 2, 2, 16, 1, tiled_f32_kernel<4, 1, 2, 2, 16, 1, false>, tiled_f32_kernel<4, 1, 2, 2, 16, 1, true>},
+    {"tiled_f32_256x64_c8", 4, 1, 2, 2, 8, 0, tiled_f32_kernel<4, 1, 2, 2, 8, 0, false>, tiled_f32_kernel<4, 1, 2, 2, 8, 0, true>},
+    {"tiled_f32_128x64_c8", 4, 1, 1, 2, 8, 0, tiled_f32_kernel<4, 1, 1, 2, 8, 0, false>, tiled_f32_kernel<4, 1, 1, 2, 8, 0, true>},
+    {"tiled_f32_128x32_c8", 4, 1, 1, 1, 8, 0, tiled_f32_kernel<4, 1, 1, 1, 8, 0, false>, tiled_f32_kernel<4, 1, 1, 1, 8, 0, true>},
+    {"tiled_f32_128x32_c2", 4, 1, 1, 1, 2, 0, tiled_f32_kernel<4, 1, 1, 1, 2, 0, false>, nullptr},
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 constexpr int LDS_LIMIT = 64 * 1024;        // two blocks per compute unit and room to spare
 
-bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, Geom* out)
+bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, bool aligned16, Geom* out)
 {
     const int taps = a.R * a.S;
     const int KT = v.WN * v.TN * 32, PT = v.WM * v.TM * 32;
@@ -305,11 +375,21 @@ bool plan(const ConvArgs& a, const Variant& v, int NB, int TH, Geom* out)
     // (Wo-1)*stride_w + (S-1)*dil_w of the padded row
     const int need = (a.Wo - 1) * a.stride_w + (a.S - 1) * a.dil_w + 1;
     g.WP = a.W + 2 * a.pad_w > need ? a.W + 2 * a.pad_w : need;
+    g.cg = a.C / a.groups;
+    // vector staging: 16-byte pieces of image rows and of a filter's chunk row must start on 16-byte
+    // boundaries in device memory and (image rows) in LDS, and chunks must be whole
+    g.vec = v.kern_vec != nullptr && aligned16 && a.W % 4 == 0 && g.cg % v.CC == 0 && (v.CC * taps) % 4 == 0 &&
+            (long long)v.CC * NB * g.PH * (a.W / 4) <= (long long)XV * THREADS && (long long)KT * v.CC * taps / 4 <= (long long)WV * THREADS;
+    if (g.vec) {
+        g.xorg = (4 - a.pad_w % 4) % 4;                // image column 0 at float xorg + pad_w of a row: a multiple of 4
+        g.WP = (g.xorg + g.WP + 3) & ~3;
+        g.x_units = v.CC * NB * g.PH * (a.W / 4);
+        g.w_units = KT * v.CC * taps / 4;
+    }
     // a fragment read takes channel c from lanes 0-31 and channel c+1 from lanes 32-63: 32 floats from the
     // middle of one plane and 32 from the next, which share no LDS bank if planes are 32 (mod 64) floats apart
     long long plane = (long long)NB * g.PH * g.WP;
     plane += (32 - plane % 64 + 64) % 64;
-    g.cg = a.C / a.groups;
     g.kg = a.K / a.groups;
     g.kb_per_group = (g.kg + KT - 1) / KT;
     g.k_blocks = g.kb_per_group * a.groups;
@@ -359,7 +439,7 @@ bool tiled_f32_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
         const int hi = multi ? PT / HoWo : PT / a.Wo;
         for (int t = hi, tried = 0; t >= 1 && tried < 8; --t) {
             tf32::Geom g;
-            if (!tf32::plan(a, v, multi ? t : 1, multi ? a.Ho : t, &g)) continue;
+            if (!tf32::plan(a, v, multi ? t : 1, multi ? a.Ho : t, env.aligned16, &g)) continue;
             ++tried;
             // Estimated cycles: blocks run two to a compute unit and share its matrix pipe; a block's chunk
             // costs its MFMAs (64 cycles each per wave) over a measured efficiency (on the 56x56 3x3 layer the
@@ -367,7 +447,8 @@ bool tiled_f32_plan(const ConvArgs& a, const PlanEnv& env, LaunchPlan* out)
             // plus a fixed hand-over per chunk.
             const long long blocks = (long long)g.row_blocks * g.img_blocks * g.k_blocks;
             const long long rounds = (blocks + 2LL * env.cus - 1) / (2LL * env.cus);
-            const double eff = (v.TM * v.TN == 4 ? 0.8 : v.TM * v.TN == 2 ? 1.0 : 0.7) * (v.TAPS > 0 ? 1.0 : 0.87);
+            // (with vector staging the 256x64 tile no longer runs short of registers: 90 against 95 us)
+            const double eff = (v.TM * v.TN == 4 ? (g.vec ? 1.0 : 0.8) : v.TM * v.TN == 2 ? 1.0 : 0.7) * (v.TAPS > 0 ? 1.0 : 0.87);
             const double chunk = (v.CC / 2) * (double)(a.R * a.S) * v.TM * v.TN * 64.0 / eff + 600.0;
             const double c = (double)rounds * 2.0 * g.n_stages * chunk;
             if (c < best) {
@@ -393,8 +474,11 @@ hipError_t tiled_f32_prepare()
 {
     static const hipError_t status = [] {
         for (int i = 0; i < tf32::kNumVariants; ++i) {
-            hipError_t e = hipFuncSetAttribute((const void*)tf32::kVariants[i].kern, hipFuncAttributeMaxDynamicSharedMemorySize, tf32::LDS_LIMIT);
-            if (e != hipSuccess) return e;
+            for (auto kern : {tf32::kVariants[i].kern, tf32::kVariants[i].kern_vec}) {
+                if (!kern) continue;
+                hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, tf32::LDS_LIMIT);
+                if (e != hipSuccess) return e;
+            }
         }
         return hipSuccess;
     }();
@@ -407,7 +491,7 @@ hipError_t tiled_f32_launch(const ConvArgs& a, const LaunchPlan& p, hipStream_t 
     if (e != hipSuccess) return e;
     tf32::Geom g;
     memcpy(&g, p.geom, sizeof g);
-    hipLaunchKernelGGL(tf32::kVariants[p.variant].kern, dim3(p.grid_x), dim3(p.block), p.lds, s, a, g);
+    hipLaunchKernelGGL(g.vec ? tf32::kVariants[p.variant].kern_vec : tf32::kVariants[p.variant].kern, dim3(p.grid_x), dim3(p.block), p.lds, s, a, g);
     return hipGetLastError();
 }
 

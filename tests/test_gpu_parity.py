@@ -60,6 +60,16 @@ def test_buffers_that_are_only_element_aligned(base, which):
     assert name.startswith("direct_"), name
 
 
+@pytest.mark.parametrize("which", ["x", "w", "y"])
+def test_fp32_buffers_that_are_only_element_aligned(which):
+    """fp32 data one element off a 16-byte boundary stays on the matrix-instruction kernel, which then
+    stages its chunks element by element instead of in 16-byte pieces."""
+    w = wl.small_variant(wl.WORKLOADS["c2"], N=2, H=28, W=28, C=24, K=40, dtype=wl.F32)
+    off = tuple(1 if which == n else 0 for n in "xwy")
+    assert check_case(w, offsets=off).startswith("tiled_f32_")
+    assert check_case(w).startswith("tiled_f32_")
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c4"])
 def test_full_size_configs_generic_kernel(name):
     w = wl.WORKLOADS[name]
