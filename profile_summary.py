@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Turns rocprofv3 output into the short summaries under profiles/.
 
-    python profile_summary.py c2 c5a ...        # reads gpurun_out/prof_<layer>/, writes profiles/<layer>_<kernel>.md
-    python profile_summary.py --sq c2 c5a ...   # reads gpurun_out/prof_<layer>/sq/, writes profiles/sq_lds_counters_all_layers.md
+    python profile_summary.py c2 c5a ...        # reads <RESULTS>/prof_<layer>/, writes profiles/<layer>_<kernel>.md
+    python profile_summary.py --sq c2 c5a ...   # reads <RESULTS>/prof_<layer>/sq/, writes profiles/sq_lds_counters_all_layers.md
     python profile_summary.py --commands c2     # prints the rocprofv3 commands whose output it expects
 
 Per layer it expects four runs of bench.py under rocprofv3 (each its own run; counters are never
@@ -28,13 +28,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 import workloads as wl  # noqa: E402
 
+RESULTS = "gpurun_out"             # folder (under the repository root) the profiling runs write into
 COPY_KIB = 256 * 1024
 SQ_COUNTERS = ("SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE SQ_LDS_ADDR_CONFLICT SQ_LDS_UNALIGNED_STALL "
                "SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_ACTIVE_INST_LDS SQ_WAIT_INST_LDS")
 
 
 def commands(name):
-    d = "gpurun_out/prof_%s" % name
+    d = "%s/prof_%s" % (RESULTS, name)
     b = "python3 bench.py --workload %s --no-layers --no-cpu" % name
     return [
         "rocprofv3 --kernel-trace --stats -d %s/trace -o trace -- %s --steps 500 --warmup 5" % (d, b),
@@ -59,7 +60,7 @@ def one_db(d, sub):
 
 
 def summarise(name):
-    d = os.path.join(ROOT, "gpurun_out", "prof_" + name)
+    d = os.path.join(ROOT, RESULTS, "prof_" + name)
     w = wl.WORKLOADS[name]
     tdb, fdb, wdb = one_db(d, "trace"), one_db(d, "fetch"), one_db(d, "write")
     top = q(tdb, "select name,total_calls,total_duration,average,percentage from top_kernels")
@@ -147,7 +148,7 @@ each output element written once): %.2f MB; ratio %.3f.
 def summarise_sq(names):
     rows = []
     for name in names:
-        db = one_db(os.path.join(ROOT, "gpurun_out", "prof_" + name), "sq")
+        db = one_db(os.path.join(ROOT, RESULTS, "prof_" + name), "sq")
         vals = {}
         kernel = None
         for k, cn, v in q(db, "select kernel_name, counter_name, avg(value) from counters_collection "
