@@ -70,6 +70,39 @@ def test_fp32_buffers_that_are_only_element_aligned(which):
     assert check_case(w).startswith("tiled_f32_")
 
 
+def test_tensors_over_two_gibibytes_take_the_generic_kernel():
+    """x and y of 2.15 GB each (the fast kernels index bytes in 32 bits and decline): every output is
+    written, and 4000 sampled outputs -- the four corners of the last plane and the last elements among
+    them -- agree with the oracle computed point by point."""
+    import torch
+    from oracle import conv_oracle
+    N, C, H, W, K = 1, 8, 11600, 11600, 8
+    w = wl.small_variant(wl.WORKLOADS["c2"], name="over_2gib", N=N, C=C, H=H, W=W, K=K)
+    say("case %s: N=%d C=%d H=%d W=%d K=%d" % (w.name, N, C, H, W, K))
+    rng = np.random.default_rng(5)
+    block = wl.to_storage(rng.uniform(0, 1, 1 << 22).astype(np.float32), wl.BF16)
+    x = np.resize(block, N * C * H * W).reshape(N, C, H, W)          # a seeded 4M-element block, repeated
+    wt = wl.to_storage(rng.normal(0, np.sqrt(2 / (C * 9)), (K, C, 3, 3)).astype(np.float32), wl.BF16)
+    b = wl.to_storage(rng.uniform(-0.1, 0.1, K).astype(np.float32), wl.BF16)
+    dx, dw, db = to_device(x, wl.BF16), to_device(wt, wl.BF16), to_device(b, wl.BF16)
+    y = torch.full((N, K, H, W), float("nan"), dtype=dx.dtype, device="cuda")
+    info = {}
+    cvx.conv_fwd_fused(dx, dw, db, pad=w.pad, stride=w.stride, dil=w.dil, act=cvx.CVX_ACT_RELU, out=y, info=info)
+    torch.cuda.synchronize()
+    assert info["kernel"].startswith("direct_"), info["kernel"]
+    assert not torch.isnan(y).any().item()
+    idx = np.stack([np.zeros(4000, np.int64), rng.integers(0, K, 4000), rng.integers(0, H, 4000), rng.integers(0, W, 4000)], 1).astype(np.int32)
+    idx[:8] = [[0, 0, 0, 0], [0, K - 1, H - 1, W - 1], [0, K - 1, H - 1, 0], [0, K - 1, 0, W - 1], [0, 0, H - 1, W - 1],
+               [0, 3, H // 2, W // 2], [0, K - 1, H - 2, W - 2], [0, K - 1, H - 1, W - 3]]
+    ref = conv_oracle.conv_fwd_points(wl.to_f64(x, wl.BF16), wl.to_f64(wt, wl.BF16), wl.to_f64(b, wl.BF16), idx,
+                                      pad=w.pad, stride=w.stride, dil=w.dil, act=1)
+    bits = y.view(torch.int16)[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy().view(np.uint16)
+    got = wl.to_f64(bits, wl.BF16)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    bad = np.abs(got - ref) > 1e-2 * np.abs(ref) + 1e-3 * rms
+    assert not bad.any(), "%d of %d sampled outputs outside tolerance" % (int(bad.sum()), len(ref))
+
+
 @pytest.mark.parametrize("name", ["c1", "c2", "c4"])
 def test_full_size_configs_generic_kernel(name):
     w = wl.WORKLOADS[name]
