@@ -590,7 +590,13 @@ igemm_kernel(ConvArgs a, IgemmGeom g)
             const int py = g.by_wo.div(rem);
             const int px = rem - py * a.Wo;
             const bool valid = f < npix;
-            xl[tm] = valid ? py * a.stride_h * g.WP + px * a.stride_w : 0;
+            // Rows of a tile past the block's pixels still go through the matrix pipe.  They are pointed at
+            // zeros where the layout has them -- the columns after the image's last one (right padding, the
+            // spare columns of the rounded pitch, the next row's left padding) -- because the chip runs at
+            // its power limit and multiplying zeros costs less of it than multiplying whatever sits at
+            // element 0.
+            const int zero_col = (g.WP - a.W >= (a.S - 1) * a.dil_w + 1) ? a.W + a.pad_w : 0;
+            xl[tm] = valid ? py * a.stride_h * g.WP + px * a.stride_w : zero_col;
             xr[tm] = (valid ? img * g.PSLOTS * 16 : 0) + half * oct_bytes;
 #pragma unroll
             for (int sw = 0; sw < NSW; ++sw) xb[tm][sw] = xr[tm] + lds_slot(xl[tm] + sw * a.dil_w) * 16;
